@@ -1,0 +1,165 @@
+// C ABI of the library: argument checks, then kernel launches on the caller's stream.
+#include "../../include/critiprefill.h"
+#include "kernels.h"
+
+#include <cmath>
+
+namespace {
+
+constexpr int kMaxBlocks = 8192;     // score kernel keeps four logit rows in LDS; select keeps a row in registers
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int make_shape(const critiprefill_params* p, cp::Shape* sh) {
+    if (!p) return CP_ERR_NULL;
+    if (p->batch <= 0 || p->n_q_heads <= 0 || p->n_kv_heads <= 0 || p->seq_len <= 0 || p->segment_size <= 0 ||
+        p->block_size <= 0 || p->budget_blocks < 0 || p->local_blocks < 0)
+        return CP_ERR_SHAPE;
+    if (p->n_q_heads % p->n_kv_heads != 0 || p->segment_size % p->block_size != 0) return CP_ERR_SHAPE;
+    if (!(p->attn_scale >= 0.f) || !(p->score_scale >= 0.f)) return CP_ERR_SHAPE;
+    if (p->head_dim != cp::kHeadDim) return CP_ERR_UNSUPPORTED;
+    if (p->dtype != CP_DTYPE_FP32 && p->dtype != CP_DTYPE_BF16) return CP_ERR_UNSUPPORTED;
+    if (p->softmax_domain != 0 && p->softmax_domain != 1) return CP_ERR_UNSUPPORTED;
+    sh->batch = p->batch; sh->hq = p->n_q_heads; sh->hkv = p->n_kv_heads; sh->n = p->seq_len;
+    sh->s = p->segment_size; sh->b = p->block_size; sh->r = sh->s / sh->b;
+    sh->n1 = (sh->n + sh->s - 1) / sh->s; sh->n2 = (sh->n + sh->b - 1) / sh->b;
+    sh->budget = p->budget_blocks; sh->local = p->local_blocks;
+    const long long ll = (long long)sh->budget + sh->local + sh->r;
+    if (ll * sh->b >= (1ll << 31) || ll > (1 << 24)) return CP_ERR_UNSUPPORTED;
+    if ((long long)sh->batch * sh->hq * sh->n1 * ((sh->s + 31) / 32) >= (1ll << 31)) return CP_ERR_UNSUPPORTED;
+    sh->list_len = (int)ll;
+    sh->dtype = p->dtype;
+    const float dflt = 1.0f / std::sqrt((float)p->head_dim);
+    sh->attn_scale = p->attn_scale > 0.f ? p->attn_scale : dflt;
+    sh->score_scale = p->score_scale > 0.f ? p->score_scale : dflt;
+    sh->alpha = p->alpha;
+    sh->softmax_domain = p->softmax_domain;
+    for (int i = 0; i < 3; ++i) {
+        sh->qs[i] = p->q_stride[i]; sh->kvs[i] = p->kv_stride[i]; sh->os[i] = p->o_stride[i];
+    }
+    return CP_OK;
+}
+
+int check_strides(const int64_t* s, int n_tokens_min_stride) {
+    for (int i = 0; i < 3; ++i)
+        if (s[i] < 0 || (s[i] & 7)) return CP_ERR_ALIGN;
+    if (s[2] < n_tokens_min_stride) return CP_ERR_SHAPE;
+    return CP_OK;
+}
+
+int check_attn(const cp::Shape& sh, const void* q, const void* k, const void* v, const void* out, const float* lse) {
+    if (!q || !k || !v || !out) return CP_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || (lse && !aligned16(lse)))
+        return CP_ERR_ALIGN;
+    int e;
+    if ((e = check_strides(sh.qs, cp::kHeadDim)) != CP_OK) return e;
+    if ((e = check_strides(sh.kvs, cp::kHeadDim)) != CP_OK) return e;
+    if ((e = check_strides(sh.os, cp::kHeadDim)) != CP_OK) return e;
+    return CP_OK;
+}
+
+size_t rep_bytes(const cp::Shape& sh, size_t* krep_offset) {
+    const size_t esz = sh.dtype == CP_DTYPE_BF16 ? 2 : 4;
+    size_t qb = (size_t)sh.batch * sh.hq * sh.n1 * 2 * cp::kHeadDim * esz;
+    qb = (qb + 255) & ~(size_t)255;
+    const size_t kb = (size_t)sh.batch * sh.hkv * sh.n2 * 2 * cp::kHeadDim * esz;
+    if (krep_offset) *krep_offset = qb;
+    return qb + kb;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t critiprefill_list_len(const critiprefill_params* p) {
+    cp::Shape sh;
+    const int e = make_shape(p, &sh);
+    return e == CP_OK ? sh.list_len : e;
+}
+
+size_t critiprefill_workspace_bytes(const critiprefill_params* p) {
+    cp::Shape sh;
+    if (make_shape(p, &sh) != CP_OK) return 0;
+    return rep_bytes(sh, nullptr);
+}
+
+int critiprefill_estimate(const critiprefill_params* p, const void* q, const void* k, const float* prev_scores,
+                          float* scores, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    cp::Shape sh;
+    int e = make_shape(p, &sh);
+    if (e != CP_OK) return e;
+    if (!q || !k || !scores || !workspace) return CP_ERR_NULL;
+    if (sh.n2 > kMaxBlocks) return CP_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(scores) || !aligned16(workspace) ||
+        (prev_scores && !aligned16(prev_scores)))
+        return CP_ERR_ALIGN;
+    if ((e = check_strides(sh.qs, cp::kHeadDim)) != CP_OK) return e;
+    if ((e = check_strides(sh.kvs, cp::kHeadDim)) != CP_OK) return e;
+    size_t koff = 0;
+    if (workspace_bytes < rep_bytes(sh, &koff)) return CP_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    void* qrep = workspace;
+    void* krep = (char*)workspace + koff;
+    if (cp::launch_pool(sh, q, k, qrep, krep, st) != hipSuccess) return CP_ERR_LAUNCH;
+    if (cp::launch_score(sh, qrep, krep, prev_scores, scores, st) != hipSuccess) return CP_ERR_LAUNCH;
+    return CP_OK;
+}
+
+int critiprefill_select(const critiprefill_params* p, const float* scores, int32_t* block_idx, int32_t* block_cnt,
+                        void* hip_stream) {
+    cp::Shape sh;
+    const int e = make_shape(p, &sh);
+    if (e != CP_OK) return e;
+    if (!scores || !block_idx || !block_cnt) return CP_ERR_NULL;
+    if (sh.n2 > kMaxBlocks) return CP_ERR_UNSUPPORTED;
+    if (!aligned16(scores) || !aligned16(block_idx) || !aligned16(block_cnt)) return CP_ERR_ALIGN;
+    if (cp::launch_select(sh, scores, block_idx, block_cnt, (hipStream_t)hip_stream) != hipSuccess)
+        return CP_ERR_LAUNCH;
+    return CP_OK;
+}
+
+int critiprefill_sparse_attn(const critiprefill_params* p, const void* q, const void* k, const void* v,
+                             const int32_t* block_idx, const int32_t* block_cnt, void* out, float* lse,
+                             void* hip_stream) {
+    cp::Shape sh;
+    int e = make_shape(p, &sh);
+    if (e != CP_OK) return e;
+    if (!block_idx || !block_cnt) return CP_ERR_NULL;
+    if ((e = check_attn(sh, q, k, v, out, lse)) != CP_OK) return e;
+    if (!aligned16(block_idx) || !aligned16(block_cnt)) return CP_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const hipError_t he = sh.dtype == CP_DTYPE_BF16
+                              ? cp::launch_attn_bf16(sh, q, k, v, block_idx, block_cnt, out, lse, st)
+                              : cp::launch_attn_fp32(sh, q, k, v, block_idx, block_cnt, out, lse, st);
+    return he == hipSuccess ? CP_OK : CP_ERR_LAUNCH;
+}
+
+int critiprefill_dense_causal_attn(const critiprefill_params* p, const void* q, const void* k, const void* v,
+                                   void* out, float* lse, void* hip_stream) {
+    cp::Shape sh;
+    int e = make_shape(p, &sh);
+    if (e != CP_OK) return e;
+    if ((e = check_attn(sh, q, k, v, out, lse)) != CP_OK) return e;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const hipError_t he = sh.dtype == CP_DTYPE_BF16
+                              ? cp::launch_attn_bf16(sh, q, k, v, nullptr, nullptr, out, lse, st)
+                              : cp::launch_attn_fp32(sh, q, k, v, nullptr, nullptr, out, lse, st);
+    return he == hipSuccess ? CP_OK : CP_ERR_LAUNCH;
+}
+
+const char* critiprefill_strerror(int status) {
+    switch (status) {
+        case CP_OK: return "ok";
+        case CP_ERR_NULL: return "a required pointer is NULL";
+        case CP_ERR_SHAPE: return "invalid shape parameters";
+        case CP_ERR_UNSUPPORTED: return "unsupported configuration";
+        case CP_ERR_ALIGN: return "pointer or stride alignment";
+        case CP_ERR_WORKSPACE: return "workspace too small";
+        case CP_ERR_LAUNCH: return "kernel launch failed";
+        default: return "unknown status";
+    }
+}
+
+int critiprefill_version(void) { return 100; }
+
+}  // extern "C"

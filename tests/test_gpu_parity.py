@@ -1,0 +1,193 @@
+"""GPU parity: every entry point of the C ABI against the fp64 CPU checker on the same seeded inputs.
+
+Bars: block lists bit-exact when both sides rank the same fp32 scores; end to end (GPU scores vs
+checker scores) equal outside a 1e-3 relative tie band around the k-th score; attention outputs
+max-abs <= 2e-2 (bf16) / 1e-4 (fp32).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import critiprefill_oracle as O
+from paper_2409_12490_amd import binding as B
+from paper_2409_12490_amd import synth
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+SMALL = [
+    # name                    B Hq Hkv   n    s    b  k  L  dtype
+    ("bf16_ragged_b64",       1, 4, 2, 1500, 256,  64, 4, 1, "bf16"),
+    ("bf16_b32_gqa4",         2, 4, 1, 1024, 128,  32, 6, 0, "bf16"),
+    ("bf16_b16_small_seg",    1, 2, 2,  777,  64,  16, 5, 2, "bf16"),
+    ("bf16_b128_seg512",      1, 2, 1, 2048, 512, 128, 3, 1, "bf16"),
+    ("bf16_seg_eq_block",     1, 2, 2,  640,  64,  64, 2, 1, "bf16"),
+    ("fp32_c1_like",          1, 2, 1, 1000, 128,  32, 8, 0, "fp32"),
+    ("fp32_b8",               1, 3, 3,  300,  32,   8, 4, 1, "fp32"),
+]
+
+
+def make(case, **kw):
+    name, B_, Hq, Hkv, n, s, b, k, L, dtype = case
+    w = H.small_workload(name, B_, Hq, Hkv, n, s, b, k, L, dtype=dtype, unit_variance=(dtype == "bf16"), **kw)
+    q, k_, v = synth.make_qkv(w, threads=4)
+    return w, q, k_, v
+
+
+def oracle_lists(w, q, k):
+    S = O.estimate(synth.to_f64(q), synth.to_f64(k), w.segment_size, w.block_size)
+    Sd = O.scores_in_decision_precision(S)
+    idx, cnt = O.select(Sd, w.segment_size, w.block_size, w.budget_blocks, w.local_blocks)
+    return S, Sd, idx, cnt
+
+
+@pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
+def test_estimate_scores(case):
+    w, q, k, v = make(case)
+    print("case", case, flush=True)
+    qf, kf = synth.to_f64(q), synth.to_f64(k)
+    for domain in (0, 1):
+        S_o = O.estimate(qf, kf, w.segment_size, w.block_size, softmax_domain=domain)
+        S_g = H.gpu_estimate(w, q.to(DEV), k.to(DEV), softmax_domain=domain).cpu().numpy()
+        np.testing.assert_allclose(S_g, S_o, rtol=2e-4, atol=1e-30)
+    # literal listing (no 1/sqrt(d)) and layer fusion with alpha = 0.25
+    S_o = O.estimate(qf, kf, w.segment_size, w.block_size, score_scale=0.05)
+    S_g = H.gpu_estimate(w, q.to(DEV), k.to(DEV), score_scale=0.05).cpu().numpy()
+    np.testing.assert_allclose(S_g, S_o, rtol=2e-4, atol=1e-30)
+    prev = np.random.default_rng(0).random(S_o.shape).astype(np.float32)
+    S_f = O.estimate(qf, kf, w.segment_size, w.block_size, prev_scores=prev.astype(np.float64), alpha=0.25)
+    w2 = w.replace(alpha=0.25)
+    S_g = H.gpu_estimate(w2, q.to(DEV), k.to(DEV), prev=torch.from_numpy(prev).to(DEV)).cpu().numpy()
+    np.testing.assert_allclose(S_g, S_f, rtol=2e-4, atol=1e-30)
+
+
+@pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
+def test_select_bit_exact_on_same_scores(case):
+    w, q, k, v = make(case)
+    print("case", case, flush=True)
+    S, Sd, idx_o, cnt_o = oracle_lists(w, q, k)
+    Sd = Sd.copy()
+    # plant exact ties and zeros so the tie-break and the k-th = 0 case are exercised
+    Sd[..., 1::3] = Sd[..., 0:-1:3][..., :Sd[..., 1::3].shape[-1]]
+    Sd[:, :, -1, : Sd.shape[-1] // 2] = 0.0
+    idx_o, cnt_o = O.select(Sd, w.segment_size, w.block_size, w.budget_blocks, w.local_blocks)
+    idx_g, cnt_g = H.gpu_select(w, q.to(DEV), k.to(DEV), torch.from_numpy(Sd).to(DEV))
+    H.check_selection(Sd, idx_o, cnt_o, idx_g, cnt_g, w, exact=True)
+
+
+def test_select_negative_and_large_budget():
+    w = H.small_workload("sel", 1, 2, 1, 4096, 64, 16, 300, 3)
+    g = np.random.default_rng(5)
+    Sd = (g.standard_normal((1, 2, w.n_segments, w.n_blocks)) * 1e-3).astype(np.float32)   # fused scores may be any sign
+    idx_o, cnt_o = O.select(Sd, w.segment_size, w.block_size, w.budget_blocks, w.local_blocks)
+    q = torch.empty((1, 2, w.seq_len, 128), dtype=torch.bfloat16, device=DEV)
+    k = torch.empty((1, 1, w.seq_len, 128), dtype=torch.bfloat16, device=DEV)
+    idx_g, cnt_g = H.gpu_select(w, q, k, torch.from_numpy(Sd).to(DEV))
+    H.check_selection(Sd, idx_o, cnt_o, idx_g, cnt_g, w, exact=True)
+
+
+@pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
+def test_estimate_then_select_tie_band(case):
+    w, q, k, v = make(case)
+    print("case", case, flush=True)
+    S, Sd, idx_o, cnt_o = oracle_lists(w, q, k)
+    S_g = H.gpu_estimate(w, q.to(DEV), k.to(DEV))
+    idx_g, cnt_g = H.gpu_select(w, q.to(DEV), k.to(DEV), S_g)
+    H.check_selection(Sd, idx_o, cnt_o, idx_g, cnt_g, w, exact=False)
+
+
+@pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
+def test_sparse_attention_with_checker_lists(case):
+    w, q, k, v = make(case)
+    print("case", case, flush=True)
+    _, _, idx_o, cnt_o = oracle_lists(w, q, k)
+    o_ref, lse_ref = O.sparse_attention(synth.to_f64(q), synth.to_f64(k), synth.to_f64(v), idx_o, cnt_o,
+                                        w.segment_size, w.block_size)
+    out, lse = H.gpu_sparse(w, q.to(DEV), k.to(DEV), v.to(DEV),
+                            torch.from_numpy(idx_o).to(DEV), torch.from_numpy(cnt_o).to(DEV))
+    err = H.max_abs(out.float().cpu().numpy(), o_ref)
+    print("max abs err", err, flush=True)
+    assert err <= H.TOL_OUT[w.dtype]
+    assert H.max_abs(lse.cpu().numpy(), lse_ref) <= (2e-2 if w.dtype == "bf16" else 1e-4)
+
+
+@pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
+def test_dense_causal_attention(case):
+    w, q, k, v = make(case)
+    print("case", case, flush=True)
+    o_ref, lse_ref = O.dense_causal_attention(synth.to_f64(q), synth.to_f64(k), synth.to_f64(v))
+    out, lse = H.gpu_dense(w, q.to(DEV), k.to(DEV), v.to(DEV))
+    err = H.max_abs(out.float().cpu().numpy(), o_ref)
+    print("max abs err", err, flush=True)
+    assert err <= H.TOL_OUT[w.dtype]
+    assert H.max_abs(lse.cpu().numpy(), lse_ref) <= (2e-2 if w.dtype == "bf16" else 1e-4)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_full_budget_reproduces_dense_on_gpu(dtype):
+    w = H.small_workload("fullbudget", 1, 2, 1, 900, 128, 32, 64, 0, dtype=dtype, unit_variance=(dtype == "bf16"))
+    q, k, v = (t.to(DEV) for t in synth.make_qkv(w, threads=2))
+    S = H.gpu_estimate(w, q, k)
+    idx, cnt = H.gpu_select(w, q, k, S)
+    o_s, lse_s = H.gpu_sparse(w, q, k, v, idx, cnt)
+    o_d, lse_d = H.gpu_dense(w, q, k, v)
+    # same tiles in the same order -> identical arithmetic
+    assert torch.equal(o_s, o_d)
+    assert torch.equal(lse_s, lse_d)
+
+
+def test_degenerate_lists_and_strided_views():
+    """Empty lists give zeros / -inf; a list without the diagonal leaves early rows empty; non-contiguous
+    head-interleaved [B, n, H, d] storage is addressed through the strides."""
+    w = H.small_workload("degenerate", 1, 2, 2, 512, 128, 32, 2, 0)
+    q0, k0, v0 = synth.make_qkv(w, threads=2)
+    # token-major storage: [B, n, H, d] viewed as [B, H, n, d]
+    q = q0.permute(0, 2, 1, 3).contiguous().to(DEV).permute(0, 2, 1, 3)
+    k = k0.permute(0, 2, 1, 3).contiguous().to(DEV).permute(0, 2, 1, 3)
+    v = v0.permute(0, 2, 1, 3).contiguous().to(DEV).permute(0, 2, 1, 3)
+    ll = w.list_len
+    idx = np.full((1, 2, w.n_segments, ll), -1, np.int32); cnt = np.zeros((1, 2, w.n_segments), np.int32)
+    idx[0, 0, 2, :2] = [0, 9]; cnt[0, 0, 2] = 2          # block 9 starts inside segment 2: partial rows
+    idx[0, 1, 3, :3] = [1, 2, 15]; cnt[0, 1, 3] = 3
+    o_ref, lse_ref = O.sparse_attention(synth.to_f64(q0), synth.to_f64(k0), synth.to_f64(v0), idx, cnt,
+                                        w.segment_size, w.block_size)
+    out = torch.full((1, w.seq_len, 2, 128), float("nan"), dtype=torch.bfloat16, device=DEV).permute(0, 2, 1, 3)
+    p = H.params_for(w, q, k, out=out)
+    lse = torch.full((1, 2, w.seq_len), float("nan"), dtype=torch.float32, device=DEV)
+    B.critiprefill_sparse_attn(p, q, k, v, torch.from_numpy(idx).to(DEV), torch.from_numpy(cnt).to(DEV), out, lse)
+    torch.cuda.synchronize()
+    assert H.max_abs(out.float().cpu().numpy(), o_ref) <= 2e-2
+    got = lse.cpu().numpy()
+    assert np.array_equal(np.isneginf(got), np.isneginf(lse_ref))
+    fin = np.isfinite(lse_ref)
+    assert H.max_abs(got[fin], lse_ref[fin]) <= 2e-2
+    # the same strided tensors through estimate
+    S_o = O.estimate(synth.to_f64(q0), synth.to_f64(k0), w.segment_size, w.block_size)
+    S_g = H.gpu_estimate(w, q, k).cpu().numpy()
+    np.testing.assert_allclose(S_g, S_o, rtol=2e-4, atol=1e-30)
+
+
+def test_c1_full_config():
+    """BASELINE config 1 in full: fp32, 1 head, 2048 tokens, segment 128, block 32, budget 8 + diagonal."""
+    w = synth.WORKLOADS["c1_fp32_2k"]
+    q, k, v = synth.make_qkv(w, threads=2)
+    qf, kf, vf = synth.to_f64(q), synth.to_f64(k), synth.to_f64(v)
+    S = O.estimate(qf, kf, w.segment_size, w.block_size)
+    Sd = O.scores_in_decision_precision(S)
+    idx_o, cnt_o = O.select(Sd, w.segment_size, w.block_size, w.budget_blocks, w.local_blocks)
+    qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
+    S_g = H.gpu_estimate(w, qd, kd)
+    np.testing.assert_allclose(S_g.cpu().numpy(), S, rtol=2e-4, atol=1e-30)
+    idx_g, cnt_g = H.gpu_select(w, qd, kd, S_g)
+    H.check_selection(Sd, idx_o, cnt_o, idx_g, cnt_g, w, exact=False)
+    o_ref, _ = O.sparse_attention(qf, kf, vf, idx_o, cnt_o, w.segment_size, w.block_size)
+    out, _ = H.gpu_sparse(w, qd, kd, vd, torch.from_numpy(idx_o).to(DEV), torch.from_numpy(cnt_o).to(DEV))
+    err = H.max_abs(out.cpu().numpy(), o_ref)
+    print("c1 sparse max abs err", err, flush=True)
+    assert err <= 1e-4
+    d_ref, _ = O.dense_causal_attention(qf, kf, vf)
+    dout, _ = H.gpu_dense(w, qd, kd, vd)
+    err = H.max_abs(dout.cpu().numpy(), d_ref)
+    print("c1 dense max abs err", err, flush=True)
+    assert err <= 1e-4
