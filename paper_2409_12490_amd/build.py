@@ -13,11 +13,15 @@ SOURCES = ["api.hip", "estimate.hip", "select.hip", "attn_fp32.hip", "attn_bf16.
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# attn_bf16: MFMA results stay in architectural VGPRs (S^T feeds the softmax VALU code directly; the
+# operands that only MFMA touches live in AGPRs), and fmaxf needs no NaN-quieting pre-pass (the kernel
+# never produces NaN: masked logits are -inf and the running max is guarded).
+EXTRA = {"attn_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1", "-fno-honor-nans", "-mno-amdgpu-ieee"]}
 
 
 def _compile(src: str, objdir: str) -> str:
     obj = os.path.join(objdir, src.replace(".hip", ".o"))
-    cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC, *FLAGS, *EXTRA.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         sys.stderr.write(r.stdout + r.stderr)

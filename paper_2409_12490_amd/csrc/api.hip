@@ -55,6 +55,12 @@ int check_attn(const cp::Shape& sh, const void* q, const void* k, const void* v,
     if ((e = check_strides(sh.qs, cp::kHeadDim)) != CP_OK) return e;
     if ((e = check_strides(sh.kvs, cp::kHeadDim)) != CP_OK) return e;
     if ((e = check_strides(sh.os, cp::kHeadDim)) != CP_OK) return e;
+    if (sh.dtype == CP_DTYPE_BF16) {
+        // the bf16 kernel addresses K/V rows with 32-bit byte offsets from the (batch, head) base
+        const long long tok_bytes = (long long)sh.kvs[2] * 2;
+        if (tok_bytes >= (1 << 24) || sh.n >= (1 << 24) || (long long)sh.n * tok_bytes >= (1ll << 32))
+            return CP_ERR_UNSUPPORTED;
+    }
     return CP_OK;
 }
 

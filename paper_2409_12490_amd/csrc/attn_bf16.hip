@@ -2,19 +2,27 @@
 // (block-sparse, gathered K/V tiles) and Eq. 2 dense causal attention (no list) from one kernel body.
 //
 // Workgroup = 4 wave64 = 256 query rows of one segment (sparse) or of the sequence (dense); a wave owns
-// 64 rows as two 32-row MFMA tiles.  The key loop walks 64-token tiles of the "virtual" token list
+// 64 rows as two 32-row MFMA sub-tiles.  The key loop walks 64-token tiles of the "virtual" token list
 // (the listed blocks laid end to end).  Per tile and wave:
 //
 //   S^T[key][q] = K_tile . Q^T      32x32x16 bf16 MFMA, A = K rows from LDS (ds_read_b128), B = Q
 //                                   fragments that stay in registers for the whole kernel.
 //   online softmax                  S^T puts one query per lane column, so row max / row sum are
-//                                   in-lane reductions plus one exchange between the wave halves.
+//                                   in-lane reductions plus one v_permlane32_swap between wave halves.
 //   O^T[ch][q] += V^T . P^T         A = V read from LDS through the transposing ds_read_b64_tr_b16,
 //                                   B = P^T taken straight from the S^T accumulators (the key order
 //                                   inside a 16-key MFMA step is chosen so no shuffle is needed).
 //
-// K/V tiles are staged global -> registers -> LDS, double buffered, one barrier per tile.
+// The two sub-tiles are software-pipelined against each other so that the softmax VALU work of one
+// overlaps the MFMA work of the other:  A: QK(0) | B: QK(1) + softmax(0) | C: PV(0) + softmax(1) | D: PV(1).
+//
+// K/V tiles go global -> LDS directly (global_load_lds_dwordx4, no register staging), double buffered,
+// one barrier per tile.  Rows are 256 B with the 16-byte chunks XOR-swizzled by the row index instead
+// of padded (the DMA writes 1 KiB contiguous per wave instruction), which keeps both the 16 B row
+// reads of K and the transposed 8 B reads of V free of bank conflicts.
 #include "kernels.h"
+
+#include <type_traits>
 
 namespace cp {
 namespace {
@@ -23,12 +31,16 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 v4bf16_lds;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+#define LDS_PTR(T, off) ((__attribute__((address_space(3))) T*)(uintptr_t)(off))
 
-constexpr int TQ = 256;     // query rows per workgroup
-constexpr int TK = 64;      // key tokens per tile
-constexpr int KP = 136;     // K row pitch in LDS, bf16 elements (272 B: conflict-free 16 B row reads)
-constexpr int VP = 144;     // V row pitch in LDS (288 B: conflict-free transposed 8 B reads)
-constexpr int kSmemBytes = 2 * TK * KP * 2 + 2 * TK * VP * 2 + 2 * TK * 4;
+constexpr int TQ = 256;               // query rows per workgroup
+constexpr int TK = 64;                // key tokens per tile
+constexpr int kTileBytes = TK * 256;  // one K or V tile in LDS
+constexpr int kVOff = 2 * kTileBytes;
+constexpr int kTokOff = 4 * kTileBytes;
+constexpr int kSmemBytes = kTokOff + 2 * TK * 4;
 
 struct ArgsB {
     const uint16_t* q; const uint16_t* k; const uint16_t* v; const int32_t* idx; const int32_t* cnt;
@@ -41,15 +53,45 @@ struct ArgsB {
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) {
     union { uint4 u; bf16x8 b; } c; c.u = v; return c.b;
 }
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
+    union { u32x4 u; bf16x8 b; } c; c.u = v; return c.b;
+}
+// Keep a value live (and computed) at this point of the program: stops the compiler from sinking the
+// producer below a later branch or from leaving a load pending into the loop.
+__device__ __forceinline__ void pin(const bf16x8& v) { asm volatile("" ::"v"(v)); }
+__device__ __forceinline__ void pin_acc(const bf16x8& v) { asm volatile("" ::"a"(v)); }
+
+// 16 bytes per lane from global memory straight into LDS at (lds_base + lane * 16); lds_base is
+// wave-uniform.  Issued through inline asm so the compiler does not serialise later LDS reads of the
+// OTHER buffer behind it; the matching s_waitcnt vmcnt(0) is issued by hand before the tile barrier.
+__device__ __forceinline__ void dma16(const void* sbase, unsigned voff, unsigned lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase)
+                 : "memory");
+}
+
+__device__ __forceinline__ const uint16_t* uniform_ptr(const uint16_t* p) {   // into SGPRs
+    const unsigned long long v = (unsigned long long)p;
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+    return (const uint16_t*)(((unsigned long long)hi << 32) | lo);
+}
+
+__device__ __forceinline__ float half_max(float x) {      // max over lanes l and l^32
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_sum(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
 
 template <bool DENSE>
 __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(ArgsB a) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    uint16_t* Ks = (uint16_t*)smem;                 // [2][TK*KP]
-    uint16_t* Vs = Ks + 2 * TK * KP;                // [2][TK*VP]
-    int* Tok = (int*)(Vs + 2 * TK * VP);            // [2][TK] token position of every tile row
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, hh = lane >> 5;
 
     // ---- which (batch, head, segment, query tile) this workgroup owns --------------------------
@@ -83,8 +125,8 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(ArgsB a) {
     const int wq_last = min(q_end, wq_lo + 64) - 1;              // < wq_lo when the wave has no rows
 
     const uint16_t* qp = a.q + bb * a.qs0 + h * a.qs1;
-    const uint16_t* kp = a.k + bb * a.ks0 + g * a.ks1;
-    const uint16_t* vp = a.v + bb * a.ks0 + g * a.ks1;
+    const uint16_t* kp = uniform_ptr(a.k + bb * a.ks0 + g * a.ks1);
+    const uint16_t* vp = uniform_ptr(a.v + bb * a.ks0 + g * a.ks1);
 
     // ---- Q fragments (B operand: column = query l32, 8 channels at 16*ks + 8*hh) ---------------
     int qpos[2];
@@ -101,6 +143,11 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(ArgsB a) {
             qf[t2][ks] = as_bf16x8(v);
         }
     }
+
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) pin_acc(qf[t2][ks]);     // Q has arrived before the key loop starts
 
     // ---- the virtual token list --------------------------------------------------------------
     const int32_t* list = nullptr; int count = 0;
@@ -123,40 +170,66 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(ArgsB a) {
         }
     }
 
-    // ---- staging: thread -> (rows r0 + 16*i, 16-byte chunk c16) of the 64 x 128 tile --------------
-    const int c16 = tid & 15, r0 = tid >> 4;
-    uint4 kr[4], vr[4]; int tk[4];
-    auto fetch = [&](int t) {
+    // ---- tile loader: wave w, instruction i fills rows 16*i + 4*w .. +3; lane -> (row, 16 B chunk) --
+    const int lrow = 4 * wave + (lane >> 4);                 // row within a 16-row group (= row & 15)
+    const int pch = lane & 15;                               // physical chunk the lane's 16 bytes land in
+    const int kch = pch ^ lrow;                              // K: chunk swizzle = row & 15
+    const int vch = pch ^ (2 * (lrow & 7));                  // V: chunk swizzle = 2 * (row & 7)
+    // The list is walked incrementally: for each of the lane's 4 rows, (e, off) = (entry, offset inside
+    // the block) of the next tile to fetch; one tile further on they advance by (64 / b, 64 % b).
+    const unsigned step_e = TK / ub, step_off = TK % ub;
+    unsigned we[4], woff[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { we[i] = (16 * i + lrow) / ub; woff[i] = (16 * i + lrow) % ub; }
+    int ent[4], eoff[4];       // block index (-1: past the list) and in-block offset of the lane's rows, fetched tile
+    auto fetch_entries = [&]() {                             // call once per tile, in tile order
+        if (DENSE) return;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int row = r0 + 16 * i;
-            const unsigned p = (unsigned)t * TK + row;
+            const int v = list[min(we[i], (unsigned)max(count - 1, 0))];
+            ent[i] = (we[i] < (unsigned)count) ? v : -1;
+            eoff[i] = (int)woff[i];
+            we[i] += step_e; woff[i] += step_off;
+            if (woff[i] >= ub) { woff[i] -= ub; we[i] += 1; }
+        }
+    };
+    // byte offsets (from kp / vp) of the lane's 4 K and 4 V chunks of a tile, and the rows' tokens
+    const unsigned tok_bytes = (unsigned)a.ks2 * 2u;         // host checks n * tok_bytes < 2^32, both < 2^24
+    unsigned koff[4], voff[4]; int tokv[4];
+    auto tile_offsets = [&](int t) {                         // sparse: uses ent/eoff fetched for tile t
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
             int tok; bool valid;
-            if (DENSE) { tok = (int)p; valid = p < total; }
-            else {
-                const unsigned e = p / ub;
-                valid = e < (unsigned)count;
-                tok = valid ? list[e] * a.b + (int)(p - e * ub) : 0;
-                valid = valid && tok < a.n;
-            }
-            kr[i] = make_uint4(0, 0, 0, 0); vr[i] = kr[i];
-            if (valid) {
-                kr[i] = *(const uint4*)(kp + (long long)tok * a.ks2 + c16 * 8);
-                vr[i] = *(const uint4*)(vp + (long long)tok * a.ks2 + c16 * 8);
-            }
-            tk[i] = valid ? tok : 0x7fffffff;
+            if (DENSE) { tok = t * TK + 16 * i + lrow; valid = (unsigned)tok < total; }
+            else { tok = ent[i] * a.b + eoff[i]; valid = ent[i] >= 0 && tok < a.n; }
+            const unsigned base = __umul24(valid ? (unsigned)tok : 0u, tok_bytes);  // invalid rows read token 0, masked later
+            koff[i] = base + kch * 16;
+            voff[i] = base + vch * 16;
+            tokv[i] = valid ? tok : 0x7fffffff;
         }
     };
-    auto stash = [&](int buf) {
-        uint16_t* kd = Ks + buf * TK * KP; uint16_t* vd = Vs + buf * TK * VP; int* td = Tok + buf * TK;
+    auto dma_k = [&](int i, int buf) { dma16(kp, koff[i], lds0 + buf * kTileBytes + (16 * i + 4 * wave) * 256); };
+    auto dma_v = [&](int i, int buf) { dma16(vp, voff[i], lds0 + kVOff + buf * kTileBytes + (16 * i + 4 * wave) * 256); };
+    auto put_tok = [&](int buf) {
+        if (pch == 0) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int row = r0 + 16 * i;
-            *(uint4*)(kd + row * KP + c16 * 8) = kr[i];
-            *(uint4*)(vd + row * VP + c16 * 8) = vr[i];
-            if (c16 == 0) td[row] = tk[i];
+            for (int i = 0; i < 4; ++i) *LDS_PTR(int, lds0 + kTokOff + buf * TK * 4 + (16 * i + lrow) * 4) = tokv[i];
         }
     };
+
+    // ---- per-lane LDS read addresses (bytes, buffer 0) -----------------------------------------
+    // K: row 32*kt + l32, logical chunk 2*ks + hh  ->  physical chunk (2*ks) ^ ((l32 & 15) ^ hh)
+    const unsigned k_row = lds0 + l32 * 256;
+    const unsigned k_swz = (unsigned)(((l32 & 15) ^ hh) << 4);
+    // V (transposed read, 16-lane groups): lane supplies row 4*hh + (i16 >> 2) (+16*t4, +8), 8-byte unit
+    // 2*(32*dt + 16*((lane>>4)&1))/8 + (i16 & 3)
+    const int i16 = lane & 15;
+    const int v_m = 4 * hh + (i16 >> 2);
+    const unsigned v_z = (unsigned)((2 * ((lane >> 4) & 1) + ((i16 & 3) >> 1)) ^ (2 * v_m));
+    unsigned v_addr[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+        v_addr[dt] = lds0 + kVOff + v_m * 256 + ((((unsigned)dt << 2) ^ v_z) << 4) + (i16 & 1) * 8;
 
     f32x16 o[4][2];
 #pragma unroll
@@ -168,123 +241,179 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(ArgsB a) {
     float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
     const float c = a.scale_log2e;
 
-    if (ntiles > 0) { fetch(0); stash(0); }
-    __syncthreads();
+    auto mask = [&](f32x16 (&s)[2], int t2, unsigned tok_base) {
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int gg = 0; gg < 4; ++gg) {
+                const i32x4 t4 = *LDS_PTR(const i32x4, tok_base + (32 * kt + 8 * gg + 4 * hh) * 4);
+                const int tv[4] = {t4[0], t4[1], t4[2], t4[3]};
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (tv[i] > qpos[t2]) s[kt][4 * gg + i] = -INFINITY;
+            }
+    };
+    auto rescale = [&](int t2, float alpha) {
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[dt][t2][r] *= alpha;
+        }
+    };
+    // pieces of the online softmax of one 64-key x 32-query sub-tile, issued between MFMAs
+    auto row_max16 = [&](const f32x16& v) {
+        float mx = fmaxf(v[0], v[1]);
+#pragma unroll
+        for (int r = 2; r < 16; ++r) mx = fmaxf(mx, v[r]);
+        return mx;
+    };
+    // new running max -> rescale factor alpha and the scaled offset ms; updates m_run
+    auto new_max = [&](int t2, float mx, float& alpha, float& ms) {
+        mx = half_max(mx);
+        const float m_new = fmaxf(m_run[t2], mx);
+        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+        alpha = __builtin_amdgcn_exp2f((m_run[t2] - m_safe) * c);
+        ms = m_safe * c;
+        m_run[t2] = m_new;
+    };
 
-    for (int t = 0; t < ntiles; ++t) {
-        const int cur = t & 1;
-        const bool more = t + 1 < ntiles;
-        if (more) fetch(t + 1);
-
-        const uint16_t* Kc = Ks + cur * TK * KP;
-        const uint16_t* Vc = Vs + cur * TK * VP;
-        const int* Tc = Tok + cur * TK;
-        const int first_tok = Tc[0], last_tok = Tc[TK - 1];
+    auto body = [&](auto bufc, int t) {
+        constexpr int BUF = decltype(bufc)::value;
+        // next tile (on the last iteration the last tile again: harmless, nobody reads that buffer)
+        tile_offsets(min(t + 1, ntiles - 1));
+        if (t + 1 < ntiles) fetch_entries();                         // entries of tile t + 2
+        put_tok(BUF ^ 1);
+        const unsigned tok_base = lds0 + kTokOff + BUF * TK * 4;
+        const int first_tok = *LDS_PTR(const int, tok_base);
+        const int last_tok = *LDS_PTR(const int, tok_base + (TK - 1) * 4);
         if (first_tok <= wq_last) {                                  // wave-uniform
-            // ---- S^T = K Q^T ----------------------------------------------------------------
-            f32x16 sacc[2][2];
+            // ---- phase A: K fragments, S^T(0) = K Q0^T -------------------------------------
+            bf16x8 kf[2][8];
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+                for (int kt = 0; kt < 2; ++kt)
+                    kf[kt][ks] = as_bf16x8(*LDS_PTR(
+                        const u32x4, (k_row + (((unsigned)ks << 5) ^ k_swz)) + BUF * kTileBytes + kt * 32 * 256));
+            f32x16 s0[2], s1[2];
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-                for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) sacc[kt][t2][r] = 0.f;
+                for (int r = 0; r < 16; ++r) { s0[kt][r] = 0.f; s1[kt][r] = 0.f; }
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) {
 #pragma unroll
-                for (int kt = 0; kt < 2; ++kt) {
-                    const bf16x8 kf = as_bf16x8(*(const uint4*)(Kc + (32 * kt + l32) * KP + 16 * ks + 8 * hh));
-#pragma unroll
-                    for (int t2 = 0; t2 < 2; ++t2)
-                        sacc[kt][t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t2][ks], sacc[kt][t2], 0, 0, 0);
-                }
-            }
-            // ---- causal / validity mask: only tiles that reach past the wave's first row ------
-            if (last_tok > wq_lo) {
-#pragma unroll
                 for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-                    for (int gg = 0; gg < 4; ++gg) {
-                        const int4 t4 = *(const int4*)(Tc + 32 * kt + 8 * gg + 4 * hh);
-                        const int tv[4] = {t4.x, t4.y, t4.z, t4.w};
-#pragma unroll
-                        for (int i = 0; i < 4; ++i)
-#pragma unroll
-                            for (int t2 = 0; t2 < 2; ++t2)
-                                if (tv[i] > qpos[t2]) sacc[kt][t2][4 * gg + i] = -INFINITY;
-                    }
+                    s0[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kt][ks], qf[0][ks], s0[kt], 0, 0, 0);
+                if (ks < 4) dma_k(ks, BUF ^ 1); else dma_v(ks - 4, BUF ^ 1);   // next tile's loads ride along
+                __builtin_amdgcn_sched_barrier(0);
             }
-            // ---- online softmax, one query per lane column ----------------------------------
-            bf16x8 pf[2][4];
-            float alpha[2];
-#pragma unroll
-            for (int t2 = 0; t2 < 2; ++t2) {
-                float mx = sacc[0][t2][0];
-#pragma unroll
-                for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[0][t2][r]);
-#pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[1][t2][r]);
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float m_new = fmaxf(m_run[t2], mx);
-                const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-                alpha[t2] = __builtin_amdgcn_exp2f((m_run[t2] - m_safe) * c);
-                const float ms = m_safe * c;
-                float rs = 0.f;
-#pragma unroll
-                for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const float p = __builtin_amdgcn_exp2f(fmaf(sacc[kt][t2][r], c, -ms));
-                        sacc[kt][t2][r] = p;
-                        rs += p;
-                    }
-                l_run[t2] = l_run[t2] * alpha[t2] + rs;          // per-half partial sums, merged at the end
-                m_run[t2] = m_new;
-                // P^T as B operand: 16-key step t4 = 2*kt + gp takes register groups 2*gp and 2*gp+1
-#pragma unroll
-                for (int t4 = 0; t4 < 4; ++t4) {
-                    const int kt = t4 >> 1, base = 8 * (t4 & 1);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) pf[t2][t4][e] = (__bf16)sacc[kt][t2][base + e];
-                }
-            }
-            if (__builtin_amdgcn_ballot_w64(alpha[0] != 1.0f || alpha[1] != 1.0f) != 0) {
-#pragma unroll
-                for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-                    for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) o[dt][t2][r] *= alpha[t2];
-            }
-            // ---- O^T += V^T P^T ---------------------------------------------------------------
-            const int i16 = lane & 15;
-            const uint16_t* vbase = Vc + (4 * hh + (i16 >> 2)) * VP + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
-#pragma unroll
-            for (int t4 = 0; t4 < 4; ++t4) {
+            if (last_tok > wq_lo) mask(s0, 0, tok_base);
+
+            bf16x8 vf[4][4];
+            auto read_v = [&](int t4) {
 #pragma unroll
                 for (int dt = 0; dt < 4; ++dt) {
-                    const uint16_t* p0 = vbase + (16 * t4) * VP + 32 * dt;
-                    const v4bf16_lds lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-                        (__attribute__((address_space(3))) v4bf16_lds*)(p0));
-                    const v4bf16_lds hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-                        (__attribute__((address_space(3))) v4bf16_lds*)(p0 + 8 * VP));
-                    bf16x8 vf;
+                    const unsigned ad = v_addr[dt] + BUF * kTileBytes + t4 * 16 * 256;
+                    const v4bf16_lds lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(v4bf16_lds, ad));
+                    const v4bf16_lds hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(v4bf16_lds, ad + 8 * 256));
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) { vf[e] = lo[e]; vf[4 + e] = hi[e]; }
-#pragma unroll
-                    for (int t2 = 0; t2 < 2; ++t2)
-                        o[dt][t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[t2][t4], o[dt][t2], 0, 0, 0);
+                    for (int e = 0; e < 4; ++e) { vf[t4][dt][e] = lo[e]; vf[t4][dt][4 + e] = hi[e]; }
                 }
+            };
+            // exp of values [lo, hi) of a sub-tile (value v lives in s[v >> 4][v & 15]), partial row sums
+            auto exp_range = [&](f32x16 (&s)[2], int lo, int hi, float ms, float& rs0, float& rs1) {
+#pragma unroll
+                for (int v = lo; v < hi; ++v) {
+                    const float p = __builtin_amdgcn_exp2f(fmaf(s[v >> 4][v & 15], c, -ms));
+                    s[v >> 4][v & 15] = p;
+                    if (v & 1) rs1 += p; else rs0 += p;
+                }
+            };
+            auto to_pf = [&](const f32x16 (&s)[2], bf16x8 (&pf)[4]) {
+#pragma unroll
+                for (int t4 = 0; t4 < 4; ++t4)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) pf[t4][e] = (__bf16)s[t4 >> 1][8 * (t4 & 1) + e];
+            };
+            constexpr int kLo[6] = {0, 6, 11, 16, 22, 27}, kHi[6] = {6, 11, 16, 22, 27, 32};
+
+            // ---- phase B: S^T(1) = K Q1^T (two MFMAs per step)  ||  softmax(0) ------------------
+            float alpha0, alpha1, ms, mxa, rs0 = 0.f, rs1 = 0.f;
+            bf16x8 pf0[4], pf1[4];
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+#pragma unroll
+                for (int kt = 0; kt < 2; ++kt)
+                    s1[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kt][ks], qf[1][ks], s1[kt], 0, 0, 0);
+                if (ks == 0) mxa = row_max16(s0[0]);
+                else if (ks == 1) new_max(0, fmaxf(mxa, row_max16(s0[1])), alpha0, ms);
+                else exp_range(s0, kLo[ks - 2], kHi[ks - 2], ms, rs0, rs1);
+                if (ks == 6) read_v(0);
+                if (ks == 7) read_v(1);
+                __builtin_amdgcn_sched_barrier(0);
             }
+            l_run[0] = l_run[0] * alpha0 + (rs0 + rs1);      // per-half partial sums, merged at the end
+            to_pf(s0, pf0);
+#pragma unroll
+            for (int t4 = 0; t4 < 4; ++t4) pin(pf0[t4]);
+            if (last_tok > wq_lo + 32) mask(s1, 1, tok_base);
+            rescale(0, alpha0);
+            // ---- phase C: O^T(0) += V^T P0^T (two MFMAs per step)  ||  softmax(1) -------------
+            rs0 = 0.f; rs1 = 0.f;
+#pragma unroll
+            for (int x = 0; x < 8; ++x) {
+                if (x == 0) read_v(2);
+                if (x == 1) read_v(3);
+#pragma unroll
+                for (int y = 0; y < 2; ++y) {
+                    const int t4 = x >> 1, dt = 2 * (x & 1) + y;
+                    o[dt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t4][dt], pf0[t4], o[dt][0], 0, 0, 0);
+                }
+                if (x == 0) mxa = row_max16(s1[0]);
+                else if (x == 1) new_max(1, fmaxf(mxa, row_max16(s1[1])), alpha1, ms);
+                else exp_range(s1, kLo[x - 2], kHi[x - 2], ms, rs0, rs1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            l_run[1] = l_run[1] * alpha1 + (rs0 + rs1);
+            to_pf(s1, pf1);
+#pragma unroll
+            for (int t4 = 0; t4 < 4; ++t4) pin(pf1[t4]);
+            rescale(1, alpha1);
+            // ---- phase D: O^T(1) += V^T P1^T ------------------------------------------------
+#pragma unroll
+            for (int t4 = 0; t4 < 4; ++t4)
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt)
+                    o[dt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t4][dt], pf1[t4], o[dt][1], 0, 0, 0);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { dma_k(i, BUF ^ 1); dma_v(i, BUF ^ 1); }
         }
-        if (more) stash(cur ^ 1);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this wave's part of the next tile has landed
         __syncthreads();
+    };
+
+    if (ntiles > 0) {
+        fetch_entries();                                             // tile 0
+        tile_offsets(0);
+        if (ntiles > 1) fetch_entries();                             // tile 1
+        put_tok(0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { dma_k(i, 0); dma_v(i, 0); }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    for (int t = 0; t < ntiles; t += 2) {
+        body(std::integral_constant<int, 0>{}, t);
+        if (t + 1 < ntiles) body(std::integral_constant<int, 1>{}, t + 1);
     }
 
     // ---- epilogue: O^T[ch][q] / l  ->  out[q][ch] ------------------------------------------------
 #pragma unroll
     for (int t2 = 0; t2 < 2; ++t2) {
-        const float l_tot = l_run[t2] + __shfl_xor(l_run[t2], 32);
+        const float l_tot = half_sum(l_run[t2]);
         const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
         if (qpos[t2] < q_end) {
             uint16_t* op = a.out + bb * a.os0 + h * a.os1 + (long long)qpos[t2] * a.os2;
