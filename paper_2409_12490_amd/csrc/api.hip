@@ -133,6 +133,7 @@ int critiprefill_sparse_attn(const critiprefill_params* p, const void* q, const 
     if (!block_idx || !block_cnt) return CP_ERR_NULL;
     if ((e = check_attn(sh, q, k, v, out, lse)) != CP_OK) return e;
     if (!aligned16(block_idx) || !aligned16(block_cnt)) return CP_ERR_ALIGN;
+    if (sh.dtype == CP_DTYPE_BF16 && sh.list_len > cp::kMaxListBf16) return CP_ERR_UNSUPPORTED;
     hipStream_t st = (hipStream_t)hip_stream;
     const hipError_t he = sh.dtype == CP_DTYPE_BF16
                               ? cp::launch_attn_bf16(sh, q, k, v, block_idx, block_cnt, out, lse, st)

@@ -16,8 +16,10 @@
 // The two sub-tiles are software-pipelined against each other so that the softmax VALU work of one
 // overlaps the MFMA work of the other:  A: QK(0) | B: QK(1) + softmax(0) | C: PV(0) + softmax(1) | D: PV(1).
 //
-// K/V tiles go global -> LDS directly (global_load_lds_dwordx4, no register staging), double buffered,
-// one barrier per tile.  Rows are 256 B with the 16-byte chunks XOR-swizzled by the row index instead
+// K/V tiles go global -> LDS directly (global_load_lds_dwordx4, no register staging) into a ring of three
+// buffers: tile t+2 is in flight while tile t is consumed, one barrier per tile.  The block list of the
+// segment is copied to LDS once, so the key loop itself issues no other global loads and the only
+// vmcnt waits in it are the hand-placed ones that pace the ring.  Rows are 256 B with the 16-byte chunks XOR-swizzled by the row index instead
 // of padded (the DMA writes 1 KiB contiguous per wave instruction), which keeps both the 16 B row
 // reads of K and the transposed 8 B reads of V free of bank conflicts.
 #include "kernels.h"
@@ -37,10 +39,13 @@ typedef __attribute__((ext_vector_type(4))) int i32x4;
 
 constexpr int TQ = 256;               // query rows per workgroup
 constexpr int TK = 64;                // key tokens per tile
+constexpr int NBUF = 3;               // K/V tile ring in LDS
 constexpr int kTileBytes = TK * 256;  // one K or V tile in LDS
-constexpr int kVOff = 2 * kTileBytes;
-constexpr int kTokOff = 4 * kTileBytes;
-constexpr int kSmemBytes = kTokOff + 2 * TK * 4;
+constexpr int kTokOff = 0;                         // [NBUF][TK] token position of every tile row
+constexpr int kVOff = 1024;                        // [NBUF] V tiles
+constexpr int kKOff = kVOff + NBUF * kTileBytes;   // [NBUF] K tiles
+constexpr int kListOff = kKOff + NBUF * kTileBytes;   // the segment's block list (sparse only)
+constexpr int kMaxListLds = 14336;                 // entries; longer lists are rejected by the API
 
 struct ArgsB {
     const uint16_t* q; const uint16_t* k; const uint16_t* v; const int32_t* idx; const int32_t* cnt;
@@ -150,11 +155,13 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(ArgsB a) {
         for (int ks = 0; ks < 8; ++ks) pin_acc(qf[t2][ks]);     // Q has arrived before the key loop starts
 
     // ---- the virtual token list --------------------------------------------------------------
-    const int32_t* list = nullptr; int count = 0;
+    int count = 0;
     if (!DENSE) {
         const long long lrow = ((long long)bb * a.hq + h) * a.n1 + j;
-        list = a.idx + lrow * a.list_len;
+        const int32_t* list = a.idx + lrow * a.list_len;
         count = a.cnt[lrow];
+        for (int x = tid; x < count; x += 256) *LDS_PTR(int, lds0 + kListOff + x * 4) = list[x];
+        __syncthreads();
     }
     // positions 0 .. total-1 of the listed blocks laid end to end (host checks count * b < 2^31)
     const unsigned total = DENSE ? (unsigned)q_last + 1u : (unsigned)count * (unsigned)a.b;
@@ -164,7 +171,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(ArgsB a) {
         while (ntiles > 0) {
             const unsigned p = (unsigned)(ntiles - 1) * TK;
             const unsigned e = p / ub;
-            const int tok = list[e] * a.b + (int)(p - e * ub);
+            const int tok = *LDS_PTR(const int, lds0 + kListOff + e * 4) * a.b + (int)(p - e * ub);
             if (tok <= q_last) break;
             --ntiles;
         }
@@ -182,33 +189,35 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(ArgsB a) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) { we[i] = (16 * i + lrow) / ub; woff[i] = (16 * i + lrow) % ub; }
     int ent[4], eoff[4];       // block index (-1: past the list) and in-block offset of the lane's rows, fetched tile
+    int dense_tile = 0;        // dense: the tile the next tile_offsets() call describes
     auto fetch_entries = [&]() {                             // call once per tile, in tile order
         if (DENSE) return;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int v = list[min(we[i], (unsigned)max(count - 1, 0))];
+            const int v = *LDS_PTR(const int, lds0 + kListOff + min(we[i], (unsigned)max(count - 1, 0)) * 4);
             ent[i] = (we[i] < (unsigned)count) ? v : -1;
             eoff[i] = (int)woff[i];
             we[i] += step_e; woff[i] += step_off;
             if (woff[i] >= ub) { woff[i] -= ub; we[i] += 1; }
         }
     };
-    // byte offsets (from kp / vp) of the lane's 4 K and 4 V chunks of a tile, and the rows' tokens
+    // byte offsets (from kp / vp) of the lane's 4 K and 4 V chunks of the next tile, and the rows' tokens
     const unsigned tok_bytes = (unsigned)a.ks2 * 2u;         // host checks n * tok_bytes < 2^32, both < 2^24
     unsigned koff[4], voff[4]; int tokv[4];
-    auto tile_offsets = [&](int t) {                         // sparse: uses ent/eoff fetched for tile t
+    auto tile_offsets = [&]() {                              // call once per tile, in tile order, before fetch_entries
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             int tok; bool valid;
-            if (DENSE) { tok = t * TK + 16 * i + lrow; valid = (unsigned)tok < total; }
+            if (DENSE) { tok = dense_tile * TK + 16 * i + lrow; valid = (unsigned)tok < total; }
             else { tok = ent[i] * a.b + eoff[i]; valid = ent[i] >= 0 && tok < a.n; }
             const unsigned base = __umul24(valid ? (unsigned)tok : 0u, tok_bytes);  // invalid rows read token 0, masked later
             koff[i] = base + kch * 16;
             voff[i] = base + vch * 16;
             tokv[i] = valid ? tok : 0x7fffffff;
         }
+        ++dense_tile;
     };
-    auto dma_k = [&](int i, int buf) { dma16(kp, koff[i], lds0 + buf * kTileBytes + (16 * i + 4 * wave) * 256); };
+    auto dma_k = [&](int i, int buf) { dma16(kp, koff[i], lds0 + kKOff + buf * kTileBytes + (16 * i + 4 * wave) * 256); };
     auto dma_v = [&](int i, int buf) { dma16(vp, voff[i], lds0 + kVOff + buf * kTileBytes + (16 * i + 4 * wave) * 256); };
     auto put_tok = [&](int buf) {
         if (pch == 0) {
@@ -219,8 +228,10 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(ArgsB a) {
 
     // ---- per-lane LDS read addresses (bytes, buffer 0) -----------------------------------------
     // K: row 32*kt + l32, logical chunk 2*ks + hh  ->  physical chunk (2*ks) ^ ((l32 & 15) ^ hh)
-    const unsigned k_row = lds0 + l32 * 256;
-    const unsigned k_swz = (unsigned)(((l32 & 15) ^ hh) << 4);
+    unsigned k_addr[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+        k_addr[ks] = lds0 + kKOff + l32 * 256 + (((unsigned)ks << 5) ^ (unsigned)(((l32 & 15) ^ hh) << 4));
     // V (transposed read, 16-lane groups): lane supplies row 4*hh + (i16 >> 2) (+16*t4, +8), 8-byte unit
     // 2*(32*dt + 16*((lane>>4)&1))/8 + (i16 & 3)
     const int i16 = lane & 15;
@@ -278,25 +289,30 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(ArgsB a) {
         m_run[t2] = m_new;
     };
 
+    bf16x8 kf[2][8];                                         // K fragments of the tile about to be consumed
+    auto read_k = [&](int buf) {
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt)
+                kf[kt][ks] = as_bf16x8(*LDS_PTR(const u32x4, k_addr[ks] + buf * kTileBytes + kt * 32 * 256));
+    };
+
+    // One tile.  On entry: tile t sits in ring slot BUF with its K fragments already in kf, tile t+1 is
+    // in flight into slot BUF+1, the DMA offsets of tile t+2 are in koff/voff (its row tokens already in
+    // LDS) and the list entries of tile t+3 are in ent/eoff.
     auto body = [&](auto bufc, int t) {
         constexpr int BUF = decltype(bufc)::value;
-        // next tile (on the last iteration the last tile again: harmless, nobody reads that buffer)
-        tile_offsets(min(t + 1, ntiles - 1));
-        if (t + 1 < ntiles) fetch_entries();                         // entries of tile t + 2
-        put_tok(BUF ^ 1);
+        constexpr int BUF1 = (BUF + 1) % NBUF, BUF2 = (BUF + 2) % NBUF;
         const unsigned tok_base = lds0 + kTokOff + BUF * TK * 4;
         const int first_tok = *LDS_PTR(const int, tok_base);
         const int last_tok = *LDS_PTR(const int, tok_base + (TK - 1) * 4);
-        if (first_tok <= wq_last) {                                  // wave-uniform
-            // ---- phase A: K fragments, S^T(0) = K Q0^T -------------------------------------
-            bf16x8 kf[2][8];
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks)
-#pragma unroll
-                for (int kt = 0; kt < 2; ++kt)
-                    kf[kt][ks] = as_bf16x8(*LDS_PTR(
-                        const u32x4, (k_row + (((unsigned)ks << 5) ^ k_swz)) + BUF * kTileBytes + kt * 32 * 256));
-            f32x16 s0[2], s1[2];
+        const bool active = first_tok <= wq_last;                    // wave-uniform
+        f32x16 s1[2];
+        bf16x8 vf[4][4], pf1[4];
+        if (active) {
+            // ---- phase A: S^T(0) = K Q0^T, the loads of tile t+2 ride along ------------------
+            f32x16 s0[2];
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
@@ -306,12 +322,11 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(ArgsB a) {
 #pragma unroll
                 for (int kt = 0; kt < 2; ++kt)
                     s0[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kt][ks], qf[0][ks], s0[kt], 0, 0, 0);
-                if (ks < 4) dma_k(ks, BUF ^ 1); else dma_v(ks - 4, BUF ^ 1);   // next tile's loads ride along
+                if (ks < 4) dma_k(ks, BUF2); else dma_v(ks - 4, BUF2);
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (last_tok > wq_lo) mask(s0, 0, tok_base);
 
-            bf16x8 vf[4][4];
             auto read_v = [&](int t4) {
 #pragma unroll
                 for (int dt = 0; dt < 4; ++dt) {
@@ -341,7 +356,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(ArgsB a) {
 
             // ---- phase B: S^T(1) = K Q1^T (two MFMAs per step)  ||  softmax(0) ------------------
             float alpha0, alpha1, ms, mxa, rs0 = 0.f, rs1 = 0.f;
-            bf16x8 pf0[4], pf1[4];
+            bf16x8 pf0[4];
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) {
 #pragma unroll
@@ -381,34 +396,51 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(ArgsB a) {
 #pragma unroll
             for (int t4 = 0; t4 < 4; ++t4) pin(pf1[t4]);
             rescale(1, alpha1);
-            // ---- phase D: O^T(1) += V^T P1^T ------------------------------------------------
+        } else {
 #pragma unroll
-            for (int t4 = 0; t4 < 4; ++t4)
+            for (int i = 0; i < 4; ++i) { dma_k(i, BUF2); dma_v(i, BUF2); }
+        }
+        // tile t+1 has landed (this wave's rows): at most the 8 loads of tile t+2 may still be in flight.
+        // After the barrier nobody reads slot BUF any more and everybody's rows of tile t+1 are in LDS.
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        __syncthreads();
+        if (active) {
+            // ---- phase D: O^T(1) += V^T P1^T  ||  K fragments of tile t+1, loader state of tile t+3 ----
+            read_k(BUF1);
+#pragma unroll
+            for (int t4 = 0; t4 < 4; ++t4) {
 #pragma unroll
                 for (int dt = 0; dt < 4; ++dt)
                     o[dt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t4][dt], pf1[t4], o[dt][1], 0, 0, 0);
+                if (t4 == 0) { tile_offsets(); put_tok(BUF); }
+                if (t4 == 1) fetch_entries();
+                __builtin_amdgcn_sched_barrier(0);
+            }
         } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) { dma_k(i, BUF ^ 1); dma_v(i, BUF ^ 1); }
+            tile_offsets(); put_tok(BUF); fetch_entries();
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this wave's part of the next tile has landed
-        __syncthreads();
     };
 
+    // ---- prologue: tiles 0 and 1 in flight, loader state primed for tile 2 and entries of tile 3 ----
     if (ntiles > 0) {
-        fetch_entries();                                             // tile 0
-        tile_offsets(0);
-        if (ntiles > 1) fetch_entries();                             // tile 1
-        put_tok(0);
+        fetch_entries();
+        tile_offsets(); fetch_entries(); put_tok(0);
 #pragma unroll
         for (int i = 0; i < 4; ++i) { dma_k(i, 0); dma_v(i, 0); }
+        tile_offsets(); fetch_entries(); put_tok(1);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { dma_k(i, 1); dma_v(i, 1); }
+        tile_offsets(); fetch_entries(); put_tok(2);
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");             // tile 0 has landed
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    for (int t = 0; t < ntiles; t += 2) {
+    if (ntiles > 0) read_k(0);
+    for (int t = 0; t < ntiles; t += 3) {
         body(std::integral_constant<int, 0>{}, t);
         if (t + 1 < ntiles) body(std::integral_constant<int, 1>{}, t + 1);
+        if (t + 2 < ntiles) body(std::integral_constant<int, 2>{}, t + 2);
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                 // no DMA may outlive the workgroup
 
     // ---- epilogue: O^T[ch][q] / l  ->  out[q][ch] ------------------------------------------------
 #pragma unroll
@@ -451,17 +483,18 @@ hipError_t launch_attn_bf16(const Shape& sh, const void* q, const void* k, const
     if (idx) {
         a.qtiles = (sh.s + TQ - 1) / TQ;
         const long long grid = (long long)sh.batch * sh.hq * sh.n1 * a.qtiles;
-        e = hipFuncSetAttribute((const void*)attn_bf16_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kSmemBytes);
+        if (sh.list_len > kMaxListLds) return hipErrorInvalidValue;
+        const int smem = kListOff + ((sh.list_len * 4 + 1023) & ~1023);
+        e = hipFuncSetAttribute((const void*)attn_bf16_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(attn_bf16_kernel<false>, dim3((unsigned)grid), dim3(256), kSmemBytes, st, a);
+        hipLaunchKernelGGL(attn_bf16_kernel<false>, dim3((unsigned)grid), dim3(256), smem, st, a);
     } else {
         a.qtiles = (sh.n + TQ - 1) / TQ;
         const long long grid = (long long)sh.batch * sh.hq * a.qtiles;
         e = hipFuncSetAttribute((const void*)attn_bf16_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kSmemBytes);
+                                kListOff);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(attn_bf16_kernel<true>, dim3((unsigned)grid), dim3(256), kSmemBytes, st, a);
+        hipLaunchKernelGGL(attn_bf16_kernel<true>, dim3((unsigned)grid), dim3(256), kListOff, st, a);
     }
     return hipGetLastError();
 }
