@@ -6,7 +6,7 @@
 namespace cp {
 
 constexpr int kHeadDim = 128;
-constexpr int kMaxListBf16 = 14336;   // block-list entries the bf16 attention kernel keeps in LDS
+constexpr int kMaxListBf16 = 6144;    // block-list entries the bf16 attention kernel keeps in LDS
 
 struct Shape {
     int batch, hq, hkv, n, s, b, r, n1, n2;   // r = s / b
