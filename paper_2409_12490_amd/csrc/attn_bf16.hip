@@ -15,7 +15,7 @@
 //
 // One wave cannot overlap its own MFMA and VALU work to any useful degree on this hardware, two waves
 // on one SIMD can.  So every SIMD holds two waves (w and w+4) that run the three phases in rotated order:
-//     waves 0-3:  QK(t)  SM(t)  PV(t)            waves 4-7:  SM(t)  PV(t)  QK(t+1)
+//     waves 0-3:  QK(t)  SM(t)  PV(t)            waves 4-7:  PV(t)  QK(t+1)  SM(t+1)
 // which puts the softmax VALU work of one wave under the MFMA work of the other.
 //
 // K/V tiles go global -> LDS directly (global_load_lds_dwordx4, no register staging) into a ring of four
@@ -91,8 +91,11 @@ __device__ __forceinline__ float half_sum(float x) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-template <bool DENSE>
+// MODE 0: sparse, any block size (row tokens of every tile kept in LDS); MODE 1: sparse, block size a
+// multiple of 64 (every tile is 64 consecutive tokens, described by its first token alone); MODE 2: dense.
+template <int MODE>
 __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
+    constexpr bool DENSE = MODE == 2, FAST = MODE != 0;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
@@ -179,16 +182,33 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
     const int pch = lane & 15;                               // physical chunk the lane's 16 bytes land in
     const int kch = pch ^ ((4 * wave + r4) & 15);            // K: logical chunk, swizzle = row & 15
     const int vch = pch ^ (4 * r4);                          // V: logical chunk, swizzle = 4 * (row & 3)
-    // The list is walked incrementally: for each of the lane's 2 rows, (e, off) = (entry, offset inside
-    // the block) of the next tile to fetch; one tile further on they advance by (64 / b, 64 % b).
+    const unsigned tok_bytes = (unsigned)a.ks2 * 2u;         // host checks n * tok_bytes < 2^32, both < 2^24
+    unsigned koff[2], voff[2];                               // byte offsets (from kp / vp) of the lane's chunks, next tile to issue
+    auto issue_tile = [&](int slot) {                        // 4 DMA instructions per wave and tile
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            dma16(kp, koff[i], lds0 + kKOff + slot * kTileBytes + (32 * i + 4 * wave) * 256);
+            dma16(vp, voff[i], lds0 + kVOff + slot * kTileBytes + (32 * i + 4 * wave) * 256);
+        }
+    };
+
+    // MODE 0 state: the list is walked incrementally per lane row: (e, off) = (entry, offset inside the
+    // block) of the next tile to fetch; one tile further on they advance by (64 / b, 64 % b).
     const unsigned step_e = TK / ub, step_off = TK % ub;
     unsigned we[2], woff[2];
+    int ent[2], eoff[2], tokv[2];
+    // MODE 1/2 state: first token of tiles t .. t+3 (-1: no such tile) and the walk over the list.
+    int nb[4] = {-1, -1, -1, -1};
+    int walk_e = 0, walk_off = 0, dense_tile = 0;
+    unsigned lane_k[2], lane_v[2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) { we[i] = (32 * i + 4 * wave + r4) / ub; woff[i] = (32 * i + 4 * wave + r4) % ub; }
-    int ent[2], eoff[2];       // block index (-1: past the list) and in-block offset of the lane's rows, fetched tile
-    int dense_tile = 0;        // dense: the tile the next tile_offsets() call describes
-    auto fetch_entries = [&]() {                             // call once per tile, in tile order
-        if (DENSE) return;
+    for (int i = 0; i < 2; ++i) {
+        const unsigned row = 32 * i + 4 * wave + r4;
+        we[i] = row / ub; woff[i] = row % ub;
+        lane_k[i] = row * tok_bytes + kch * 16;
+        lane_v[i] = row * tok_bytes + vch * 16;
+    }
+    auto fetch_entries = [&]() {                             // MODE 0: call once per tile, in tile order
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int v = *LDS_PTR(const int, lds0 + kListOff + min(we[i], (unsigned)max(count - 1, 0)) * 4);
@@ -198,27 +218,15 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
             if (woff[i] >= ub) { woff[i] -= ub; we[i] += 1; }
         }
     };
-    // byte offsets (from kp / vp) of the lane's 2 K and 2 V chunks of the next tile, and the rows' tokens
-    const unsigned tok_bytes = (unsigned)a.ks2 * 2u;         // host checks n * tok_bytes < 2^32, both < 2^24
-    unsigned koff[2], voff[2]; int tokv[2];
-    auto tile_offsets = [&]() {                              // call once per tile, in tile order, before fetch_entries
+    auto tile_offsets = [&]() {                              // MODE 0: offsets + row tokens of the fetched tile
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            int tok; bool valid;
-            if (DENSE) { tok = dense_tile * TK + 32 * i + 4 * wave + r4; valid = (unsigned)tok < total; }
-            else { tok = ent[i] * a.b + eoff[i]; valid = ent[i] >= 0 && tok < a.n; }
+            const int tok = ent[i] * a.b + eoff[i];
+            const bool valid = ent[i] >= 0 && tok < a.n;
             const unsigned base = __umul24(valid ? (unsigned)tok : 0u, tok_bytes);  // invalid rows read token 0, masked later
             koff[i] = base + kch * 16;
             voff[i] = base + vch * 16;
             tokv[i] = valid ? tok : 0x7fffffff;
-        }
-        ++dense_tile;
-    };
-    auto issue_tile = [&](int slot) {                        // 4 DMA instructions per wave and tile
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            dma16(kp, koff[i], lds0 + kKOff + slot * kTileBytes + (32 * i + 4 * wave) * 256);
-            dma16(vp, voff[i], lds0 + kVOff + slot * kTileBytes + (32 * i + 4 * wave) * 256);
         }
     };
     auto put_tok = [&](int slot) {
@@ -226,6 +234,44 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
 #pragma unroll
             for (int i = 0; i < 2; ++i)
                 *LDS_PTR(int, lds0 + kTokOff + slot * TK * 4 + (32 * i + 4 * wave + r4) * 4) = tokv[i];
+        }
+    };
+    auto next_base = [&]() -> int {                          // MODE 1/2: first token of the next tile in order, -1 past the end
+        int base = -1;
+        if (DENSE) {
+            if (dense_tile < ntiles) base = dense_tile * TK;
+            ++dense_tile;
+        } else {
+            if (walk_e < count)
+                base = __builtin_amdgcn_readfirstlane(*LDS_PTR(const int, lds0 + kListOff + walk_e * 4)) * a.b + walk_off;
+            walk_off += TK;
+            if (walk_off >= a.b) { walk_off = 0; ++walk_e; }
+        }
+        return base;
+    };
+    auto base_offsets = [&](int base) {                      // MODE 1/2: offsets of the tile that starts at token base
+        if (base >= 0 && base + TK <= a.n) {                 // uniform: the whole tile exists
+            const unsigned sb = (unsigned)base * tok_bytes;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) { koff[i] = sb + lane_k[i]; voff[i] = sb + lane_v[i]; }
+        } else {                                             // ragged last tile or no tile: invalid rows read token 0
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int tok = base + 32 * i + 4 * wave + r4;
+                const bool valid = base >= 0 && tok < a.n;
+                const unsigned sb = __umul24(valid ? (unsigned)tok : 0u, tok_bytes);
+                koff[i] = sb + kch * 16;
+                voff[i] = sb + vch * 16;
+            }
+        }
+    };
+    // describe the next tile in order (its DMA offsets go to koff/voff); MODE 0 also publishes its row tokens
+    auto describe_next = [&](int slot) {
+        if (FAST) {
+            nb[0] = nb[1]; nb[1] = nb[2]; nb[2] = nb[3]; nb[3] = next_base();
+            base_offsets(nb[3]);
+        } else {
+            tile_offsets(); put_tok(slot); fetch_entries();
         }
     };
 
@@ -249,7 +295,14 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+    // row sums ride on the matrix core: l^T[.][q] += ones . P^T gives sum_key P[key][q] in every row
+    f32x16 lacc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) lacc[r] = 0.f;
+    bf16x8 ones;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
+    float m_run = -INFINITY;
     const float c = a.scale_log2e;
 
     // ---- the three phases ---------------------------------------------------------------------
@@ -306,7 +359,18 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
                     if (tv[i] > qpos) s[kt][4 * gg + i] = -INFINITY;
             }
     };
-    // S^T tile -> P^T fragments; running max / sum; O rescaled when any row's max moved
+    // MODE 1/2: the tile holds tokens base .. base+63; key row kr is visible iff base + kr <= min(qpos, n-1)
+    auto mask_base = [&](f32x16 (&s)[2], int base) {
+        const int lim = min(qpos, a.n - 1) - base - 4 * hh;
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int gg = 0; gg < 4; ++gg)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (32 * kt + 8 * gg + i > lim) s[kt][4 * gg + i] = -INFINITY;
+    };
+    // S^T tile -> P^T fragments; running max; O and the row sums rescaled when any row's max moved
     auto sm = [&](f32x16 (&s)[2], bf16x8 (&pf)[4]) {
         float mx = fmaxf(s[0][0], s[1][0]);
 #pragma unroll
@@ -317,16 +381,10 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
         const float alpha = __builtin_amdgcn_exp2f((m_run - m_safe) * c);
         const float ms = m_safe * c;
         m_run = m_new;
-        float rs0 = 0.f, rs1 = 0.f;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(s[kt][r], c, -ms));
-                s[kt][r] = p;
-                if (r & 1) rs1 += p; else rs0 += p;
-            }
-        l_run = l_run * alpha + (rs0 + rs1);                 // per-half partial sums, merged at the end
+            for (int r = 0; r < 16; ++r) s[kt][r] = __builtin_amdgcn_exp2f(fmaf(s[kt][r], c, -ms));
         // P^T as B operand: 16-key step t4 = 2*kt + gp takes accumulator registers 8*gp .. 8*gp+7
 #pragma unroll
         for (int t4 = 0; t4 < 4; ++t4)
@@ -337,6 +395,8 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
             for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) lacc[r] *= alpha;
         }
     };
     auto pv = [&](int slot, const bf16x8 (&pf)[4], int next_slot) {   // V group 0 of the tile must be on its way
@@ -346,27 +406,43 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt)
                 o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[t4 & 1][dt], pf[t4], o[dt], 0, 0, 0);
+            lacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf[t4], lacc, 0, 0, 0);
             if (t4 == 3 && next_slot >= 0) read_kg(next_slot, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
     auto first_tok = [&](int slot) { return *LDS_PTR(const int, lds0 + kTokOff + slot * TK * 4); };
     auto last_tok = [&](int slot) { return *LDS_PTR(const int, lds0 + kTokOff + slot * TK * 4 + (TK - 1) * 4); };
+    // tile t (ring slot) as seen by this wave: does any of its rows see the tile, does the tile need a mask
+    auto tile_active = [&](int slot, int base) {
+        return FAST ? (base >= 0 && base <= wq_last) : (first_tok(slot) <= wq_last);
+    };
+    auto mask_if_needed = [&](f32x16 (&s)[2], int slot, int base) {
+        if (FAST) { if (base + TK - 1 > wq_lo || base + TK > a.n) mask_base(s, base); }
+        else { if (last_tok(slot) > wq_lo) mask(s, slot); }
+    };
     // end of a tile step: tile t+2 has landed (this wave's rows; at most the 4 loads of tile t+3 are still in
-    // flight), then everybody is past its reads of tile t; afterwards the loader state moves on to tile t+4
-    // whose row tokens go into the slot tile t just vacated.
+    // flight), then everybody is past its reads of tile t; afterwards the loader moves on to tile t+4 (its
+    // row tokens, in MODE 0, go into the slot tile t just vacated).
     auto step_end = [&](int slot) {
+        if (FAST) describe_next(slot);                       // registers only: off the critical path
         asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
         __syncthreads();
-        tile_offsets(); put_tok(slot); fetch_entries();
+        if (!FAST) describe_next(slot);                      // writes the row tokens into the vacated slot
     };
 
-    // ---- prologue: tiles 0, 1, 2 in flight; loader state primed for tile 3, entries of tile 4 ----
+    // ---- prologue: tiles 0, 1, 2 in flight; tile 3 described ----------------------------------------
     if (ntiles > 0) {
-        fetch_entries();
+        if (FAST) {
 #pragma unroll
-        for (int s3 = 0; s3 < 3; ++s3) { tile_offsets(); fetch_entries(); put_tok(s3); issue_tile(s3); }
-        tile_offsets(); fetch_entries(); put_tok(3);
+            for (int s3 = 0; s3 < 3; ++s3) { nb[s3] = next_base(); base_offsets(nb[s3]); issue_tile(s3); }
+            nb[3] = next_base(); base_offsets(nb[3]);
+        } else {
+            fetch_entries();
+#pragma unroll
+            for (int s3 = 0; s3 < 3; ++s3) { tile_offsets(); fetch_entries(); put_tok(s3); issue_tile(s3); }
+            tile_offsets(); fetch_entries(); put_tok(3);
+        }
         asm volatile("s_waitcnt vmcnt(4)" ::: "memory");             // tiles 0 and 1 have landed
     }
     __syncthreads();
@@ -376,30 +452,29 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
         for (int t = 0; t < ntiles; ++t) {
             const int slot = t & 3;
             issue_tile((t + 3) & 3);
-            if (first_tok(slot) <= wq_last) {                        // wave-uniform; once false it stays false
+            if (tile_active(slot, nb[0])) {                          // wave-uniform; once false it stays false
                 f32x16 s[2]; bf16x8 pf[4];
                 qk(slot, s);
-                if (last_tok(slot) > wq_lo) mask(s, slot);
+                mask_if_needed(s, slot, nb[0]);
                 sm(s, pf);
                 pv(slot, pf, t + 1 < ntiles ? (t + 1) & 3 : -1);     // tile t+1 landed a step ago
             }
             step_end(slot);
         }
     } else {
+        // one tile ahead with QK and the softmax: P^T of tile t is ready when step t starts
         f32x16 s[2]; bf16x8 pf[4];
-        bool have_s = false;
-        if (ntiles > 0 && first_tok(0) <= wq_last) { read_kg(0, 0); qk(0, s); have_s = true; }
+        bool have_p = false;
+        if (ntiles > 0 && tile_active(0, nb[0])) {
+            read_kg(0, 0); qk(0, s); mask_if_needed(s, 0, nb[0]); sm(s, pf); have_p = true;
+        }
         for (int t = 0; t < ntiles; ++t) {
             const int slot = t & 3, nslot = (t + 1) & 3;
             issue_tile((t + 3) & 3);
-            const bool have_next = (t + 1 < ntiles) && first_tok(nslot) <= wq_last;
-            if (have_s) {
-                if (last_tok(slot) > wq_lo) mask(s, slot);
-                sm(s, pf);
-                pv(slot, pf, have_next ? nslot : -1);
-                if (have_next) qk(nslot, s);
-            }
-            have_s = have_s && have_next;
+            const bool have_next = have_p && (t + 1 < ntiles) && tile_active(nslot, nb[1]);
+            if (have_p) pv(slot, pf, have_next ? nslot : -1);
+            if (have_next) { qk(nslot, s); mask_if_needed(s, nslot, nb[1]); sm(s, pf); }
+            have_p = have_next;
             step_end(slot);
         }
     }
@@ -407,7 +482,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
 
     // ---- epilogue: O^T[ch][q] / l  ->  out[q][ch] ------------------------------------------------
     {
-        const float l_tot = half_sum(l_run);
+        const float l_tot = lacc[0];
         const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
         if (qpos < q_end) {
             uint16_t* op = a.out + bb * a.os0 + h * a.os1 + (long long)qpos * a.os2;
@@ -447,16 +522,22 @@ hipError_t launch_attn_bf16(const Shape& sh, const void* q, const void* k, const
         a.qtiles = (sh.s + TQ - 1) / TQ;
         const long long grid = (long long)sh.batch * sh.hq * sh.n1 * a.qtiles;
         const int smem = kListOff + ((sh.list_len * 4 + 1023) & ~1023);
-        e = hipFuncSetAttribute((const void*)attn_bf16_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(attn_bf16_kernel<false>, dim3((unsigned)grid), dim3(512), smem, st, a);
+        if (sh.b % TK == 0) {
+            e = hipFuncSetAttribute((const void*)attn_bf16_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL(attn_bf16_kernel<1>, dim3((unsigned)grid), dim3(512), smem, st, a);
+        } else {
+            e = hipFuncSetAttribute((const void*)attn_bf16_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL(attn_bf16_kernel<0>, dim3((unsigned)grid), dim3(512), smem, st, a);
+        }
     } else {
         a.qtiles = (sh.n + TQ - 1) / TQ;
         const long long grid = (long long)sh.batch * sh.hq * a.qtiles;
-        e = hipFuncSetAttribute((const void*)attn_bf16_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        e = hipFuncSetAttribute((const void*)attn_bf16_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 kListOff);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(attn_bf16_kernel<true>, dim3((unsigned)grid), dim3(512), kListOff, st, a);
+        hipLaunchKernelGGL(attn_bf16_kernel<2>, dim3((unsigned)grid), dim3(512), kListOff, st, a);
     }
     return hipGetLastError();
 }
