@@ -14,13 +14,15 @@
 //                                     inside a 16-key MFMA step is chosen so no shuffle is needed).
 //
 // One wave cannot overlap its own MFMA and VALU work to any useful degree on this hardware, two waves
-// on one SIMD can.  So every SIMD holds two waves (w and w+4) that run the three phases in rotated order:
-//     waves 0-3:  QK(t)  SM(t)  PV(t)            waves 4-7:  PV(t)  QK(t+1)  SM(t+1)
+// on one SIMD can.  So every SIMD holds two waves (w and w+4).  A wave alternates between a matrix phase
+// MM(t) = PV(t-1) interleaved with QK(t) (36 independent-enough MFMAs that keep the matrix pipe full) and the
+// softmax phase SM(t); the two waves of a SIMD run half a period apart:
+//     waves 0-3:  MM(t)  SM(t)                   waves 4-7:  SM(t)  MM(t+1)
 // which puts the softmax VALU work of one wave under the MFMA work of the other.
 //
-// K/V tiles go global -> LDS directly (global_load_lds_dwordx4, no register staging) into a ring of four
-// slots: tile t+3 is issued while tile t is consumed (the rotated waves already read K of tile t+1), one
-// barrier per tile.  Rows are 256 B with the 16-byte chunks XOR-swizzled by the row index instead of
+// K/V tiles go global -> LDS directly (global_load_lds_dwordx4, no register staging) into rings of four
+// slots each: K of tile t+3 and V of tile t+2 are issued while tile t is consumed (K of tile t+1 and V of
+// tile t-1 are still being read then), one barrier per tile.  Rows are 256 B with the 16-byte chunks XOR-swizzled by the row index instead of
 // padded (the DMA writes 1 KiB contiguous per wave instruction), which keeps both the 16 B row reads of K
 // and the transposed 8 B reads of V free of bank conflicts.  The block list of the segment is copied to
 // LDS once, so the key loop itself issues no other global loads and the only vmcnt waits in it are the
@@ -183,13 +185,16 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
     const int kch = pch ^ ((4 * wave + r4) & 15);            // K: logical chunk, swizzle = row & 15
     const int vch = pch ^ (4 * r4);                          // V: logical chunk, swizzle = 4 * (row & 3)
     const unsigned tok_bytes = (unsigned)a.ks2 * 2u;         // host checks n * tok_bytes < 2^32, both < 2^24
-    unsigned koff[2], voff[2];                               // byte offsets (from kp / vp) of the lane's chunks, next tile to issue
-    auto issue_tile = [&](int slot) {                        // 4 DMA instructions per wave and tile
+    // byte offsets (from kp / vp) of the lane's chunks: koff/voff = the tile described last; V is issued one
+    // step later than K, so its offsets wait in voff_issue
+    unsigned koff[2], voff[2], voff_issue[2];
+    auto issue_k = [&](int slot) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            dma16(kp, koff[i], lds0 + kKOff + slot * kTileBytes + (32 * i + 4 * wave) * 256);
-            dma16(vp, voff[i], lds0 + kVOff + slot * kTileBytes + (32 * i + 4 * wave) * 256);
-        }
+        for (int i = 0; i < 2; ++i) dma16(kp, koff[i], lds0 + kKOff + slot * kTileBytes + (32 * i + 4 * wave) * 256);
+    };
+    auto issue_v = [&](int slot, const unsigned (&off)[2]) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) dma16(vp, off[i], lds0 + kVOff + slot * kTileBytes + (32 * i + 4 * wave) * 256);
     };
 
     // MODE 0 state: the list is walked incrementally per lane row: (e, off) = (entry, offset inside the
@@ -267,6 +272,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
     };
     // describe the next tile in order (its DMA offsets go to koff/voff); MODE 0 also publishes its row tokens
     auto describe_next = [&](int slot) {
+        voff_issue[0] = voff[0]; voff_issue[1] = voff[1];
         if (FAST) {
             nb[0] = nb[1]; nb[1] = nb[2]; nb[2] = nb[3]; nb[3] = next_base();
             base_offsets(nb[3]);
@@ -277,10 +283,8 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
 
     // ---- per-lane LDS read addresses (bytes, ring slot 0) ----------------------------------------
     // K: row 32*kt + l32, logical chunk 2*ks + hh  ->  physical chunk (2*ks) ^ ((l32 & 15) ^ hh)
-    unsigned k_addr[8];
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
-        k_addr[ks] = lds0 + kKOff + l32 * 256 + (((unsigned)ks << 5) ^ (unsigned)(((l32 & 15) ^ hh) << 4));
+    // = k_base ^ (ks << 5): the row part has its low 8 bits clear (the LDS base is 1 KiB aligned)
+    const unsigned k_base = (lds0 + kKOff + l32 * 256) | (unsigned)(((l32 & 15) ^ hh) << 4);
     // V (transposed read, 16-lane groups): lane supplies row 4*hh + (i16 >> 2) (+16*t4, +8) and the 8-byte
     // unit of channels 32*dt + 16*gbit + 4*(i16 & 3); physical chunk = logical chunk ^ 4*(row & 3)
     const int i16 = lane & 15, gbit = (lane >> 4) & 1;
@@ -295,54 +299,77 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
-    // row sums ride on the matrix core: l^T[.][q] += ones . P^T gives sum_key P[key][q] in every row
-    f32x16 lacc;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) lacc[r] = 0.f;
-    bf16x8 ones;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
-    float m_run = -INFINITY;
+    float m_run = -INFINITY, l_run = 0.f;
     const float c = a.scale_log2e;
 
     // ---- the three phases ---------------------------------------------------------------------
     // LDS fragments are read in groups of four (4 MFMAs each) into two alternating register groups, one
-    // group ahead of their use, so that an MFMA does not wait a full LDS round trip.  QK ends by issuing
-    // the first V group of its tile and PV ends by issuing the first K group of the next tile, so the
-    // first MFMAs of the following phase find their operands on the way.
+    // group ahead of their use, so that an MFMA does not wait a full LDS round trip.  The first group of a
+    // matrix phase is issued before the softmax phase that precedes it.
     bf16x8 fr[2][4];
-    auto read_kg = [&](int slot, int gq) {                   // K group gq: ks = 2*gq, 2*gq+1, both key halves
+    auto read_kg = [&](int slot, int gq, int grp) {          // K group gq: ks = 2*gq, 2*gq+1, both key halves
 #pragma unroll
         for (int x = 0; x < 2; ++x)
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
-                fr[gq & 1][2 * x + kt] =
-                    as_bf16x8(*LDS_PTR(const u32x4, k_addr[2 * gq + x] + slot * kTileBytes + kt * 32 * 256));
+                fr[grp][2 * x + kt] =
+                    as_bf16x8(*LDS_PTR(const u32x4, (k_base ^ ((2 * gq + x) << 5)) + slot * kTileBytes + kt * 32 * 256));
     };
-    auto read_vg = [&](int slot, int t4) {                   // V group t4: 16 keys, all four channel tiles
+    auto read_vg = [&](int slot, int t4, int grp) {          // V group t4: 16 keys, all four channel tiles
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) {
             const unsigned ad = v_addr[dt] + slot * kTileBytes + t4 * 16 * 256;
             const v4bf16_lds lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(v4bf16_lds, ad));
             const v4bf16_lds hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(v4bf16_lds, ad + 8 * 256));
 #pragma unroll
-            for (int e = 0; e < 4; ++e) { fr[t4 & 1][dt][e] = lo[e]; fr[t4 & 1][dt][4 + e] = hi[e]; }
+            for (int e = 0; e < 4; ++e) { fr[grp][dt][e] = lo[e]; fr[grp][dt][4 + e] = hi[e]; }
         }
     };
-    auto qk = [&](int slot, f32x16 (&s)[2]) {                // K group 0 of the tile must be on its way
+    auto mfma_kg = [&](int gq, int grp, f32x16 (&s)[2]) {
+#pragma unroll
+        for (int x = 0; x < 2; ++x)
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt)
+                s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[grp][2 * x + kt], qf[2 * gq + x], s[kt], 0, 0, 0);
+    };
+    auto mfma_vg = [&](int t4, int grp, const bf16x8 (&pf)[4]) {
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[grp][dt], pf[t4], o[dt], 0, 0, 0);
+    };
+    auto zero_s = [&](f32x16 (&s)[2]) {
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
+    };
+    auto qk = [&](int slot, f32x16 (&s)[2]) {                // S^T = K Q^T; K group 0 already on its way into fr[0]
+        zero_s(s);
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
-            if (gq + 1 < 4) read_kg(slot, gq + 1);
+            if (gq + 1 < 4) read_kg(slot, gq + 1, (gq + 1) & 1);
+            mfma_kg(gq, gq & 1, s);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    auto pv = [&](int slot, const bf16x8 (&pf)[4]) {         // O^T += V^T P^T; V group 0 already on its way into fr[0]
 #pragma unroll
-            for (int x = 0; x < 2; ++x)
+        for (int t4 = 0; t4 < 4; ++t4) {
+            if (t4 + 1 < 4) read_vg(slot, t4 + 1, (t4 + 1) & 1);
+            mfma_vg(t4, t4 & 1, pf);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    // PV of one tile interleaved with QK of the next; V group 0 already on its way into fr[0]
+    auto mm_both = [&](int vslot, int kslot, f32x16 (&s)[2], const bf16x8 (&pf)[4]) {
+        zero_s(s);
 #pragma unroll
-                for (int kt = 0; kt < 2; ++kt)
-                    s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[gq & 1][2 * x + kt], qf[2 * gq + x], s[kt], 0, 0, 0);
-            if (gq == 3) read_vg(slot, 0);                   // into the group the MFMAs of gq = 2 have released
+        for (int i = 0; i < 4; ++i) {
+            read_kg(kslot, i, 1);
+            mfma_vg(i, 0, pf);
+            __builtin_amdgcn_sched_barrier(0);
+            if (i + 1 < 4) read_vg(vslot, i + 1, 0);
+            mfma_kg(i, 1, s);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -370,7 +397,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
                 for (int i = 0; i < 4; ++i)
                     if (32 * kt + 8 * gg + i > lim) s[kt][4 * gg + i] = -INFINITY;
     };
-    // S^T tile -> P^T fragments; running max; O and the row sums rescaled when any row's max moved
+    // S^T tile -> P^T fragments; running max / sum; O rescaled when any row's max moved
     auto sm = [&](f32x16 (&s)[2], bf16x8 (&pf)[4]) {
         float mx = fmaxf(s[0][0], s[1][0]);
 #pragma unroll
@@ -381,10 +408,16 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
         const float alpha = __builtin_amdgcn_exp2f((m_run - m_safe) * c);
         const float ms = m_safe * c;
         m_run = m_new;
+        float rs0 = 0.f, rs1 = 0.f;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s[kt][r] = __builtin_amdgcn_exp2f(fmaf(s[kt][r], c, -ms));
+            for (int r = 0; r < 16; ++r) {
+                const float p = __builtin_amdgcn_exp2f(fmaf(s[kt][r], c, -ms));
+                s[kt][r] = p;
+                if (r & 1) rs1 += p; else rs0 += p;
+            }
+        l_run = l_run * alpha + (rs0 + rs1);                 // per-half partial sums, merged at the end
         // P^T as B operand: 16-key step t4 = 2*kt + gp takes accumulator registers 8*gp .. 8*gp+7
 #pragma unroll
         for (int t4 = 0; t4 < 4; ++t4)
@@ -395,20 +428,6 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
             for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) lacc[r] *= alpha;
-        }
-    };
-    auto pv = [&](int slot, const bf16x8 (&pf)[4], int next_slot) {   // V group 0 of the tile must be on its way
-#pragma unroll
-        for (int t4 = 0; t4 < 4; ++t4) {
-            if (t4 + 1 < 4) read_vg(slot, t4 + 1);
-#pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
-                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[t4 & 1][dt], pf[t4], o[dt], 0, 0, 0);
-            lacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf[t4], lacc, 0, 0, 0);
-            if (t4 == 3 && next_slot >= 0) read_kg(next_slot, 0);
-            __builtin_amdgcn_sched_barrier(0);
         }
     };
     auto first_tok = [&](int slot) { return *LDS_PTR(const int, lds0 + kTokOff + slot * TK * 4); };
@@ -431,50 +450,61 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
         if (!FAST) describe_next(slot);                      // writes the row tokens into the vacated slot
     };
 
-    // ---- prologue: tiles 0, 1, 2 in flight; tile 3 described ----------------------------------------
+    // ---- prologue: K of tiles 0-2 and V of tiles 0-1 in flight; tiles up to 3 described -------------
     if (ntiles > 0) {
-        if (FAST) {
+        if (!FAST) fetch_entries();
 #pragma unroll
-            for (int s3 = 0; s3 < 3; ++s3) { nb[s3] = next_base(); base_offsets(nb[s3]); issue_tile(s3); }
-            nb[3] = next_base(); base_offsets(nb[3]);
-        } else {
-            fetch_entries();
-#pragma unroll
-            for (int s3 = 0; s3 < 3; ++s3) { tile_offsets(); fetch_entries(); put_tok(s3); issue_tile(s3); }
-            tile_offsets(); fetch_entries(); put_tok(3);
+        for (int s3 = 0; s3 < 4; ++s3) {
+            if (FAST) { nb[s3] = next_base(); base_offsets(nb[s3]); }
+            else { tile_offsets(); fetch_entries(); put_tok(s3); }
+            if (s3 == 0) { issue_k(0); issue_v(0, voff); }
+            if (s3 == 1) { issue_k(1); }                     // K0 V0 K1 first: they are needed at once
+            if (s3 == 1) { voff_issue[0] = voff[0]; voff_issue[1] = voff[1]; }
+            if (s3 == 2) { issue_v(1, voff_issue); issue_k(2); voff_issue[0] = voff[0]; voff_issue[1] = voff[1]; }
         }
-        asm volatile("s_waitcnt vmcnt(4)" ::: "memory");             // tiles 0 and 1 have landed
+        asm volatile("s_waitcnt vmcnt(4)" ::: "memory");             // K0, V0, K1 have landed
     }
     __syncthreads();
+    // from here on: koff = K offsets of tile 3, voff_issue = V offsets of tile 2, voff = V offsets of tile 3
 
+    f32x16 s[2]; bf16x8 pf[4];
     if (!rotated) {
-        if (ntiles > 0) read_kg(0, 0);
+        bool have_p = false;                                         // P^T of tile t-1 waits for its PV
+        bool act = ntiles > 0 && tile_active(0, nb[0]);              // wave-uniform; once false it stays false
+        if (act) read_kg(0, 0, 0);
         for (int t = 0; t < ntiles; ++t) {
-            const int slot = t & 3;
-            issue_tile((t + 3) & 3);
-            if (tile_active(slot, nb[0])) {                          // wave-uniform; once false it stays false
-                f32x16 s[2]; bf16x8 pf[4];
-                qk(slot, s);
+            const int slot = t & 3, pslot = (t - 1) & 3, nslot = (t + 1) & 3;
+            issue_v((t + 2) & 3, voff_issue);
+            issue_k((t + 3) & 3);
+            if (have_p && act) mm_both(pslot, slot, s, pf);
+            else if (act) qk(slot, s);
+            else if (have_p) pv(pslot, pf);
+            const bool act_next = act && (t + 1 < ntiles) && tile_active(nslot, nb[1]);
+            if (act) {
+                read_vg(slot, 0, 0);                                 // first group of the next matrix phase
                 mask_if_needed(s, slot, nb[0]);
                 sm(s, pf);
-                pv(slot, pf, t + 1 < ntiles ? (t + 1) & 3 : -1);     // tile t+1 landed a step ago
             }
+            have_p = act; act = act_next;
             step_end(slot);
         }
+        if (have_p) pv((ntiles - 1) & 3, pf);
     } else {
-        // one tile ahead with QK and the softmax: P^T of tile t is ready when step t starts
-        f32x16 s[2]; bf16x8 pf[4];
-        bool have_p = false;
-        if (ntiles > 0 && tile_active(0, nb[0])) {
-            read_kg(0, 0); qk(0, s); mask_if_needed(s, 0, nb[0]); sm(s, pf); have_p = true;
-        }
+        bool have_s = ntiles > 0 && tile_active(0, nb[0]);
+        if (have_s) { read_kg(0, 0, 0); qk(0, s); }
         for (int t = 0; t < ntiles; ++t) {
             const int slot = t & 3, nslot = (t + 1) & 3;
-            issue_tile((t + 3) & 3);
-            const bool have_next = have_p && (t + 1 < ntiles) && tile_active(nslot, nb[1]);
-            if (have_p) pv(slot, pf, have_next ? nslot : -1);
-            if (have_next) { qk(nslot, s); mask_if_needed(s, nslot, nb[1]); sm(s, pf); }
-            have_p = have_next;
+            issue_v((t + 2) & 3, voff_issue);
+            issue_k((t + 3) & 3);
+            const bool act_next = have_s && (t + 1 < ntiles) && tile_active(nslot, nb[1]);
+            if (have_s) {
+                read_vg(slot, 0, 0);                                 // first group of the matrix phase below
+                mask_if_needed(s, slot, nb[0]);
+                sm(s, pf);
+                if (act_next) mm_both(slot, nslot, s, pf);
+                else pv(slot, pf);
+            }
+            have_s = act_next;
             step_end(slot);
         }
     }
@@ -482,7 +512,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
 
     // ---- epilogue: O^T[ch][q] / l  ->  out[q][ch] ------------------------------------------------
     {
-        const float l_tot = lacc[0];
+        const float l_tot = half_sum(l_run);
         const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
         if (qpos < q_end) {
             uint16_t* op = a.out + bb * a.os0 + h * a.os1 + (long long)qpos * a.os2;
