@@ -249,6 +249,164 @@ __global__ __launch_bounds__(256) void score_valu_kernel(ScoreArgs a) {
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// score, bf16: the four representative products as one bf16 MFMA GEMM (representatives are exact
+// bf16 values, so every product is exact and only the fp32 accumulation rounds).
+//
+// Workgroup = 4 waves = 16 segments of one (batch, head).  A operand (32 rows) = [Q_max of the 16
+// segments ; Q_min of the 16 segments], kept in registers.  B operand = 32 blocks of K_max, then the same
+// 32 blocks of K_min, read straight from global memory (1 MiB per KV head, L2 resident).  In the 32x32
+// result a lane holds, for its block column, both query representatives of 8 segments; with the two
+// MFMA results that is all of S1..S4 for 8 (segment, block) pairs in one lane.  Wave w takes the block
+// tiles w, w+4, ...  Pass 1 finds every row's max and sum of exponentials (online, per lane, then
+// reduced over lanes and waves); pass 2 recomputes the products and writes the combined score.
+// ---------------------------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) {
+    union { uint4 u; bf16x8 b; } c; c.u = v; return c.b;
+}
+
+constexpr int kSegPerWg = 16;
+
+__global__ __launch_bounds__(256) void score_mfma_kernel(ScoreArgs a) {
+    __shared__ float red_m[4][2][2][kSegPerWg];   // [wave][a][bb][segment]
+    __shared__ float red_l[4][2][2][kSegPerWg];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, hh = lane >> 5;
+    const int j0 = blockIdx.x * kSegPerWg, h = blockIdx.y, bb_ = blockIdx.z;
+    const int g = h / (a.hq / a.hkv);
+    const long long qrow0 = ((long long)bb_ * a.hq + h) * a.n1;
+    const long long kbase = ((long long)bb_ * a.hkv + g) * a.n2;
+    constexpr float kLog2e = 1.4426950408889634f;
+    const float c = a.scale * kLog2e;                        // logits in log2 units
+
+    // A fragments: row m = l32 -> representative (m >> 4) of segment j0 + (m & 15)
+    bf16x8 qf[8];
+    {
+        const int jq = min(j0 + (l32 & 15), a.n1 - 1);
+        const uint16_t* src = (const uint16_t*)a.qrep + ((qrow0 + jq) * 2 + (l32 >> 4)) * kHeadDim + 8 * hh;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qf[ks] = as_bf16x8(*(const uint4*)(src + 16 * ks));
+    }
+    // the lane's 8 segments: register r of an accumulator is row 8*(r>>2) + 4*hh + (r&3)
+    //   representative = r >> 3, segment slot x = ((r >> 2) & 1) * 4 + (r & 3) -> segment j0 + 8*((r>>2)&1) + 4*hh + (r&3)
+    int vis[8];                                             // first block wholly after the segment
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
+        const int j = j0 + 8 * (x >> 2) + 4 * hh + (x & 3);
+        vis[x] = min(a.n2, (j + 1) * a.r);
+    }
+    const int ntile = (a.n2 + 31) / 32;
+
+    // Z for one 32-block tile: z[bb][r]
+    auto tile_z = [&](int nt, f32x16 (&z)[2]) {
+        const int i = min(nt * 32 + l32, a.n2 - 1);
+        const uint16_t* src = (const uint16_t*)a.krep + (kbase + i) * 2 * kHeadDim + 8 * hh;
+#pragma unroll
+        for (int b2 = 0; b2 < 2; ++b2) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) z[b2][r] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                const bf16x8 kf = as_bf16x8(*(const uint4*)(src + b2 * kHeadDim + 16 * ks));
+                z[b2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[ks], kf, z[b2], 0, 0, 0);
+            }
+        }
+    };
+
+    // ---- pass 1: per lane online max / sum of 2^(c z) over its block columns -------------------
+    float m[2][16], l[2][16];
+#pragma unroll
+    for (int b2 = 0; b2 < 2; ++b2)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { m[b2][r] = -INFINITY; l[b2][r] = 0.f; }
+    for (int nt = wave; nt < ntile; nt += 4) {
+        f32x16 z[2];
+        tile_z(nt, z);
+        const int i = nt * 32 + l32;
+#pragma unroll
+        for (int b2 = 0; b2 < 2; ++b2)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int x = ((r >> 2) & 1) * 4 + (r & 3);
+                const bool in_dom = i < (a.domain == 0 ? a.n2 : vis[x]);
+                const float v = in_dom ? z[b2][r] * c : -INFINITY;
+                const float mn = fmaxf(m[b2][r], v);
+                const float ms = (mn == -INFINITY) ? 0.f : mn;
+                l[b2][r] = l[b2][r] * exp2f(m[b2][r] - ms) + exp2f(v - ms);
+                m[b2][r] = mn;
+            }
+    }
+    // reduce over the 32 lanes of a half (block columns), then over the waves
+#pragma unroll
+    for (int b2 = 0; b2 < 2; ++b2)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float mm = m[b2][r], ll = l[b2][r];
+#pragma unroll
+            for (int o = 16; o > 0; o >>= 1) {
+                const float m2 = __shfl_xor(mm, o), l2 = __shfl_xor(ll, o);
+                const float mn = fmaxf(mm, m2);
+                const float ms = (mn == -INFINITY) ? 0.f : mn;
+                ll = ll * exp2f(mm - ms) + l2 * exp2f(m2 - ms);
+                mm = mn;
+            }
+            if (l32 == 0) {
+                const int seg = 8 * ((r >> 2) & 1) + 4 * hh + (r & 3);
+                red_m[wave][r >> 3][b2][seg] = mm;
+                red_l[wave][r >> 3][b2][seg] = ll;
+            }
+        }
+    __syncthreads();
+    float inv[2][16];                                       // 1 / sum, and m becomes the final max
+#pragma unroll
+    for (int b2 = 0; b2 < 2; ++b2)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int seg = 8 * ((r >> 2) & 1) + 4 * hh + (r & 3);
+            float mm = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) mm = fmaxf(mm, red_m[w][r >> 3][b2][seg]);
+            const float ms = (mm == -INFINITY) ? 0.f : mm;
+            float ll = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) ll += red_l[w][r >> 3][b2][seg] * exp2f(red_m[w][r >> 3][b2][seg] - ms);
+            m[b2][r] = ms;
+            inv[b2][r] = ll > 0.f ? 1.0f / ll : 0.f;
+        }
+
+    // ---- pass 2: recompute, normalise, combine, mask, fuse, store -------------------------------
+    for (int nt = wave; nt < ntile; nt += 4) {
+        f32x16 z[2];
+        tile_z(nt, z);
+        const int i = nt * 32 + l32;
+        if (i >= a.n2) continue;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            const int j = j0 + 8 * (x >> 2) + 4 * hh + (x & 3);
+            if (j >= a.n1) continue;
+            const int r0 = 4 * (x >> 2) + (x & 3), r1 = r0 + 8;   // Q_max row and Q_min row of the segment
+            const bool in_dom = i < (a.domain == 0 ? a.n2 : vis[x]);
+            float p[2][2];
+#pragma unroll
+            for (int b2 = 0; b2 < 2; ++b2) {
+                p[0][b2] = in_dom ? exp2f(z[b2][r0] * c - m[b2][r0]) * inv[b2][r0] : 0.f;
+                p[1][b2] = in_dom ? exp2f(z[b2][r1] * c - m[b2][r1]) * inv[b2][r1] : 0.f;
+            }
+            // S1 = (max,max), S2 = (max,min), S3 = (min,max), S4 = (min,min)
+            float sc = fmaxf((p[0][0] + p[1][0]) * 0.5f, (p[0][1] + p[1][1]) * 0.5f);
+            if (i >= vis[x]) sc = 0.f;
+            const long long off = (qrow0 + j) * a.n2 + i;
+            if (a.prev) sc = a.alpha * sc + (1.0f - a.alpha) * a.prev[off];
+            if (fabsf(sc) < 1.17549435e-38f) sc = 0.f;
+            a.scores[off] = sc;
+        }
+    }
+}
+
 }  // namespace
 
 hipError_t launch_pool(const Shape& sh, const void* q, const void* k, void* qrep, void* krep, hipStream_t st) {
@@ -272,6 +430,11 @@ hipError_t launch_score(const Shape& sh, const void* qrep, const void* krep, con
     a.qrep = qrep; a.krep = krep; a.prev = prev; a.scores = scores;
     a.hq = sh.hq; a.hkv = sh.hkv; a.n1 = sh.n1; a.n2 = sh.n2; a.r = sh.r; a.domain = sh.softmax_domain;
     a.scale = sh.score_scale; a.alpha = sh.alpha;
+    if (sh.dtype == 1) {
+        dim3 grid_m((sh.n1 + kSegPerWg - 1) / kSegPerWg, sh.hq, sh.batch);
+        hipLaunchKernelGGL(score_mfma_kernel, grid_m, dim3(256), 0, st, a);
+        return hipGetLastError();
+    }
     const size_t smem = (2 * kHeadDim + 4 + 4 * (size_t)sh.n2) * sizeof(float);
     dim3 grid(sh.n1, sh.hq, sh.batch);
     const void* fn = sh.dtype == 1 ? (const void*)score_valu_kernel<true> : (const void*)score_valu_kernel<false>;
