@@ -47,6 +47,8 @@ def main() -> int:
     ap.add_argument("--workload", default="c3_llama3_8b_128k")
     ap.add_argument("--dense-steps", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 1 GiB device copy (a known-size kernel to scale rocprofv3 FETCH_SIZE/WRITE_SIZE by)")
     ap.add_argument("--cpu-segments", type=int, default=24, help="(head, segment) pairs the CPU checker attends")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -126,6 +128,13 @@ def main() -> int:
     torch.cuda.synchronize()
     dense_ms = e0.elapsed_time(e1) / args.dense_steps
     sparse_vs_dense_err = float((out.float() - dense_out.float()).abs().max().item())
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     achieved = sparse_flop / (att_ms * 1e-3) / 1e12
     result = {
