@@ -34,6 +34,7 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 v4bf16_lds;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
@@ -408,21 +409,26 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
         const float alpha = __builtin_amdgcn_exp2f((m_run - m_safe) * c);
         const float ms = m_safe * c;
         m_run = m_new;
-        float rs0 = 0.f, rs1 = 0.f;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(s[kt][r], c, -ms));
-                s[kt][r] = p;
-                if (r & 1) rs1 += p; else rs0 += p;
-            }
-        l_run = l_run * alpha + (rs0 + rs1);                 // per-half partial sums, merged at the end
-        // P^T as B operand: 16-key step t4 = 2*kt + gp takes accumulator registers 8*gp .. 8*gp+7
+            for (int r = 0; r < 16; ++r) s[kt][r] = __builtin_amdgcn_exp2f(fmaf(s[kt][r], c, -ms));
+        // P^T as B operand: 16-key step t4 = 2*kt + gp takes accumulator registers 8*gp .. 8*gp+7.  The row
+        // sum adds up the bf16-rounded values that the PV contraction actually uses, two per instruction.
+        bf16x2 one2; one2[0] = (__bf16)1.0f; one2[1] = (__bf16)1.0f;
+        float rs0 = 0.f, rs1 = 0.f;
 #pragma unroll
-        for (int t4 = 0; t4 < 4; ++t4)
+        for (int t4 = 0; t4 < 4; ++t4) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) pf[t4][e] = (__bf16)s[t4 >> 1][8 * (t4 & 1) + e];
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {
+                bf16x2 pr; pr[0] = pf[t4][e]; pr[1] = pf[t4][e + 1];
+                if (e & 2) rs1 = __builtin_amdgcn_fdot2_f32_bf16(pr, one2, rs1, false);
+                else rs0 = __builtin_amdgcn_fdot2_f32_bf16(pr, one2, rs0, false);
+            }
+        }
+        l_run = l_run * alpha + (rs0 + rs1);                 // per-half partial sums, merged at the end
         if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt)
