@@ -50,7 +50,9 @@ constexpr int kTokOff = 0;                            // [NBUF][TK] token positi
 constexpr int kVOff = 1024;                           // [NBUF] V tiles
 constexpr int kKOff = kVOff + NBUF * kTileBytes;      // [NBUF] K tiles
 constexpr int kListOff = kKOff + NBUF * kTileBytes;   // the segment's block list (sparse only)
+constexpr int kOutPitch = 272;                        // epilogue staging: one output row + 16 B, in bytes
 static_assert(kListOff + kMaxListBf16 * 4 <= 160 * 1024, "LDS budget");
+static_assert(8 * WQ * kOutPitch <= 2 * NBUF * kTileBytes, "epilogue staging reuses the tile rings");
 
 struct ArgsB {
     const uint16_t* q; const uint16_t* k; const uint16_t* v; const int32_t* idx; const int32_t* cnt;
@@ -163,8 +165,6 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
         count = a.cnt[lrow];
         for (int x = tid; x < count; x += 512) *LDS_PTR(int, lds0 + kListOff + x * 4) = list[x];
     }
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) pin(qf[ks]);                  // Q has arrived before the key loop starts
     __syncthreads();
     // positions 0 .. total-1 of the listed blocks laid end to end (host checks count * b < 2^31)
     const unsigned total = DENSE ? (unsigned)q_last + 1u : (unsigned)count * (unsigned)a.b;
@@ -468,8 +468,10 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
             if (s3 == 1) { voff_issue[0] = voff[0]; voff_issue[1] = voff[1]; }
             if (s3 == 2) { issue_v(1, voff_issue); issue_k(2); voff_issue[0] = voff[0]; voff_issue[1] = voff[1]; }
         }
-        asm volatile("s_waitcnt vmcnt(4)" ::: "memory");             // K0, V0, K1 have landed
     }
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) pin(qf[ks]);                      // Q has arrived: no wait for it is left in the key loop
+    if (ntiles > 0) asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); // K0, V0, K1 have landed
     __syncthreads();
     // from here on: koff = K offsets of tile 3, voff_issue = V offsets of tile 2, voff = V offsets of tile 3
 
@@ -516,25 +518,31 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                 // no DMA may outlive the workgroup
 
-    // ---- epilogue: O^T[ch][q] / l  ->  out[q][ch] ------------------------------------------------
+    // ---- epilogue: O^T[ch][q] / l -> out[q][ch], transposed through LDS so that global stores are whole rows ----
     {
         const float l_tot = half_sum(l_run);
         const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-        if (qpos < q_end) {
-            uint16_t* op = a.out + bb * a.os0 + h * a.os1 + (long long)qpos * a.os2;
+        __syncthreads();                                             // every wave is past its last tile reads
+        const unsigned stage = lds0 + kVOff + wave * (WQ * kOutPitch);
 #pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
+        for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-                for (int gg = 0; gg < 4; ++gg) {
-                    bf16x4 w;
+            for (int gg = 0; gg < 4; ++gg) {
+                bf16x4 w;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) w[i] = (__bf16)(o[dt][4 * gg + i] * inv);
-                    *(bf16x4*)(op + 32 * dt + 8 * gg + 4 * hh) = w;
-                }
-            if (a.lse && hh == 0)
-                a.lse[((long long)bb * a.hq + h) * a.n + qpos] =
-                    l_tot > 0.f ? m_run * a.scale + __logf(l_tot) : -INFINITY;
+                for (int i = 0; i < 4; ++i) w[i] = (__bf16)(o[dt][4 * gg + i] * inv);
+                *LDS_PTR(bf16x4, stage + l32 * kOutPitch + (32 * dt + 8 * gg + 4 * hh) * 2) = w;
+            }
+        // the wave reads back only what it wrote itself: 4 rows of 256 B per instruction
+        uint16_t* ob = a.out + bb * a.os0 + h * a.os1;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            const int row = 4 * x + r4;
+            const u32x4 val = *LDS_PTR(const u32x4, stage + row * kOutPitch + pch * 16);
+            if (wq_lo + row < q_end) *(u32x4*)(ob + (long long)(wq_lo + row) * a.os2 + pch * 8) = val;
         }
+        if (a.lse && hh == 0 && qpos < q_end)
+            a.lse[((long long)bb * a.hq + h) * a.n + qpos] = l_tot > 0.f ? m_run * a.scale + __logf(l_tot) : -INFINITY;
     }
 }
 
