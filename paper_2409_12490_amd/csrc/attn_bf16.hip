@@ -180,7 +180,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
         }
     }
 
-    // ---- tile loader: wave w fills rows 4*w .. 4*w+3 and 32 + 4*w .. +3 of K and of V (4 instructions) ----
+    // ---- tile loader: a wave fills rows 4*w .. 4*w+3 and 32 + 4*w .. +3 of K and of V (4 instructions) ----
     const int r4 = lane >> 4;                                // row inside the wave's 4-row group
     const int pch = lane & 15;                               // physical chunk the lane's 16 bytes land in
     const int kch = pch ^ ((4 * wave + r4) & 15);            // K: logical chunk, swizzle = row & 15
@@ -188,14 +188,31 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
     const unsigned tok_bytes = (unsigned)a.ks2 * 2u;         // host checks n * tok_bytes < 2^32, both < 2^24
     // byte offsets (from kp / vp) of the lane's chunks: koff/voff = the tile described last; V is issued one
     // step later than K, so its offsets wait in voff_issue
+    // MODE 1/2: waves 0-3 also fill the rows of waves 4-7 (16 rows further down: same swizzle), which then issue
+    // no loads at all - the matrix-first waves 0-3 reach the tile barrier earlier than their partners otherwise.
+    constexpr bool SPLIT = FAST;
+    const bool loader = !SPLIT || wave < 4;
     unsigned koff[2], voff[2], voff_issue[2];
+    unsigned koff2[2], voff2[2], voff2_issue[2];             // SPLIT: the rows taken over from wave + 4
     auto issue_k = [&](int slot) {
+        if (!loader) return;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) dma16(kp, koff[i], lds0 + kKOff + slot * kTileBytes + (32 * i + 4 * wave) * 256);
+        for (int i = 0; i < 2; ++i) {
+            dma16(kp, koff[i], lds0 + kKOff + slot * kTileBytes + (32 * i + 4 * wave) * 256);
+            if (SPLIT) dma16(kp, koff2[i], lds0 + kKOff + slot * kTileBytes + (32 * i + 4 * wave + 16) * 256);
+        }
     };
-    auto issue_v = [&](int slot, const unsigned (&off)[2]) {
+    auto issue_v = [&](int slot, bool first) {               // first: straight from voff (prologue), else from voff_issue
+        if (!loader) return;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) dma16(vp, off[i], lds0 + kVOff + slot * kTileBytes + (32 * i + 4 * wave) * 256);
+        for (int i = 0; i < 2; ++i) {
+            dma16(vp, first ? voff[i] : voff_issue[i], lds0 + kVOff + slot * kTileBytes + (32 * i + 4 * wave) * 256);
+            if (SPLIT) dma16(vp, first ? voff2[i] : voff2_issue[i], lds0 + kVOff + slot * kTileBytes + (32 * i + 4 * wave + 16) * 256);
+        }
+    };
+    auto dma_wait = [&]() {                                  // all but the loads of the newest tile pair have landed
+        if (SPLIT) { if (loader) asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); }
+        else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
     };
 
     // MODE 0 state: the list is walked incrementally per lane row: (e, off) = (entry, offset inside the
@@ -259,24 +276,29 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
         if (base >= 0 && base + TK <= a.n) {                 // uniform: the whole tile exists
             const unsigned sb = (unsigned)base * tok_bytes;
 #pragma unroll
-            for (int i = 0; i < 2; ++i) { koff[i] = sb + lane_k[i]; voff[i] = sb + lane_v[i]; }
+            for (int i = 0; i < 2; ++i) {
+                koff[i] = sb + lane_k[i]; voff[i] = sb + lane_v[i];
+                koff2[i] = koff[i] + 16 * tok_bytes; voff2[i] = voff[i] + 16 * tok_bytes;
+            }
         } else {                                             // ragged last tile or no tile: invalid rows read token 0
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 const int tok = base + 32 * i + 4 * wave + r4;
-                const bool valid = base >= 0 && tok < a.n;
+                const bool valid = base >= 0 && tok < a.n, valid2 = base >= 0 && tok + 16 < a.n;
                 const unsigned sb = __umul24(valid ? (unsigned)tok : 0u, tok_bytes);
-                koff[i] = sb + kch * 16;
-                voff[i] = sb + vch * 16;
+                const unsigned sb2 = __umul24(valid2 ? (unsigned)tok + 16u : 0u, tok_bytes);
+                koff[i] = sb + kch * 16; voff[i] = sb + vch * 16;
+                koff2[i] = sb2 + kch * 16; voff2[i] = sb2 + vch * 16;
             }
         }
     };
     // describe the next tile in order (its DMA offsets go to koff/voff); MODE 0 also publishes its row tokens
     auto describe_next = [&](int slot) {
         voff_issue[0] = voff[0]; voff_issue[1] = voff[1];
+        if (SPLIT) { voff2_issue[0] = voff2[0]; voff2_issue[1] = voff2[1]; }
         if (FAST) {
             nb[0] = nb[1]; nb[1] = nb[2]; nb[2] = nb[3]; nb[3] = next_base();
-            base_offsets(nb[3]);
+            if (loader) base_offsets(nb[3]);
         } else {
             tile_offsets(); put_tok(slot); fetch_entries();
         }
@@ -450,8 +472,8 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
     // flight), then everybody is past its reads of tile t; afterwards the loader moves on to tile t+4 (its
     // row tokens, in MODE 0, go into the slot tile t just vacated).
     auto step_end = [&](int slot) {
-        if (FAST) describe_next(slot);                       // registers only: off the critical path
-        asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        if (FAST) describe_next(slot);                       // registers only
+        dma_wait();
         __syncthreads();
         if (!FAST) describe_next(slot);                      // writes the row tokens into the vacated slot
     };
@@ -463,15 +485,18 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
         for (int s3 = 0; s3 < 4; ++s3) {
             if (FAST) { nb[s3] = next_base(); base_offsets(nb[s3]); }
             else { tile_offsets(); fetch_entries(); put_tok(s3); }
-            if (s3 == 0) { issue_k(0); issue_v(0, voff); }
+            if (s3 == 0) { issue_k(0); issue_v(0, true); }
             if (s3 == 1) { issue_k(1); }                     // K0 V0 K1 first: they are needed at once
-            if (s3 == 1) { voff_issue[0] = voff[0]; voff_issue[1] = voff[1]; }
-            if (s3 == 2) { issue_v(1, voff_issue); issue_k(2); voff_issue[0] = voff[0]; voff_issue[1] = voff[1]; }
+            if (s3 == 1 || s3 == 2) {
+                if (s3 == 2) { issue_v(1, false); issue_k(2); }
+                voff_issue[0] = voff[0]; voff_issue[1] = voff[1];
+                if (SPLIT) { voff2_issue[0] = voff2[0]; voff2_issue[1] = voff2[1]; }
+            }
         }
     }
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) pin(qf[ks]);                      // Q has arrived: no wait for it is left in the key loop
-    if (ntiles > 0) asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); // K0, V0, K1 have landed
+    if (ntiles > 0) dma_wait();                                      // K0, V0, K1 have landed
     __syncthreads();
     // from here on: koff = K offsets of tile 3, voff_issue = V offsets of tile 2, voff = V offsets of tile 3
 
@@ -482,7 +507,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
         if (act) read_kg(0, 0, 0);
         for (int t = 0; t < ntiles; ++t) {
             const int slot = t & 3, pslot = (t - 1) & 3, nslot = (t + 1) & 3;
-            issue_v((t + 2) & 3, voff_issue);
+            issue_v((t + 2) & 3, false);
             issue_k((t + 3) & 3);
             if (have_p && act) mm_both(pslot, slot, s, pf);
             else if (act) qk(slot, s);
@@ -502,7 +527,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
         if (have_s) { read_kg(0, 0, 0); qk(0, s); }
         for (int t = 0; t < ntiles; ++t) {
             const int slot = t & 3, nslot = (t + 1) & 3;
-            issue_v((t + 2) & 3, voff_issue);
+            issue_v((t + 2) & 3, false);
             issue_k((t + 3) & 3);
             const bool act_next = have_s && (t + 1 < ntiles) && tile_active(nslot, nb[1]);
             if (have_s) {
