@@ -509,9 +509,11 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
             const int slot = t & 3, pslot = (t - 1) & 3, nslot = (t + 1) & 3;
             issue_v((t + 2) & 3, false);
             issue_k((t + 3) & 3);
+            __builtin_amdgcn_s_setprio(3);                               // matrix phase: its MFMAs go ahead of the partner's VALU work
             if (have_p && act) mm_both(pslot, slot, s, pf);
             else if (act) qk(slot, s);
             else if (have_p) pv(pslot, pf);
+            __builtin_amdgcn_s_setprio(0);
             const bool act_next = act && (t + 1 < ntiles) && tile_active(nslot, nb[1]);
             if (act) {
                 read_vg(slot, 0, 0);                                 // first group of the next matrix phase
@@ -534,8 +536,10 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
                 read_vg(slot, 0, 0);                                 // first group of the matrix phase below
                 mask_if_needed(s, slot, nb[0]);
                 sm(s, pf);
+                __builtin_amdgcn_s_setprio(3);
                 if (act_next) mm_both(slot, nslot, s, pf);
                 else pv(slot, pf);
+                __builtin_amdgcn_s_setprio(0);
             }
             have_s = act_next;
             step_end(slot);
