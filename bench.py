@@ -49,7 +49,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device copy (a known-size kernel to scale rocprofv3 FETCH_SIZE/WRITE_SIZE by)")
-    ap.add_argument("--cpu-segments", type=int, default=24, help="(head, segment) pairs the CPU checker attends")
+    ap.add_argument("--cpu-heads", type=int, default=8, help="query heads the CPU checker estimates, selects and attends")
+    ap.add_argument("--cpu-segments", type=int, default=1280, help="(head, segment) pairs the CPU checker attends, over all sampled heads")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
@@ -163,10 +164,11 @@ def main() -> int:
     }
 
     if not args.no_cpu_baseline:
-        # the CPU checker as it stands, on a bounded sample: Algorithm 1 + top-k for 2 query heads, then the
-        # pruned attention of a few (head, segment) pairs; scaled to one whole layer.
+        # the CPU checker as it stands, on a bounded sample (10-30 s of CPU work): Algorithm 1 + top-k for a few
+        # query heads, then the pruned attention of some of their segments; scaled linearly to one whole layer.
         from oracle import critiprefill_oracle as O
-        heads = [0, w.n_q_heads - 1]
+        nh = max(1, min(args.cpu_heads, w.n_q_heads))
+        heads = sorted(set(int(round(i * (w.n_q_heads - 1) / max(nh - 1, 1))) for i in range(nh)))
         G = w.n_q_heads // w.n_kv_heads
         t0 = time.perf_counter()
         lists = {}
@@ -176,7 +178,8 @@ def main() -> int:
             lists[h] = O.select(O.scores_in_decision_precision(S_o), s, b, w.budget_blocks, w.local_blocks)
         t_est = time.perf_counter() - t0
         rng = np.random.default_rng(0)
-        segs = sorted(set(int(x) for x in rng.integers(w.n_segments // 2, w.n_segments, size=args.cpu_segments // 2)))
+        per_head = max(1, args.cpu_segments // len(heads))
+        segs = sorted(int(x) for x in rng.choice(np.arange(w.n_segments // 4, w.n_segments), size=min(per_head, w.n_segments - w.n_segments // 4), replace=False))
         t0 = time.perf_counter()
         worst = 0.0
         n_done = 0
