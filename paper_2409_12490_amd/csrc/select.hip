@@ -46,7 +46,8 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a) {
 #pragma unroll
     for (int m = 0; m < PER_LANE; ++m) {
         const int i = m * 64 + lane;
-        key[m] = (i < n_cand) ? ordered_key(s[i]) : 0u;   // only compared where i < n_cand
+        const uint32_t kx = ordered_key(s[min(i, a.n2 - 1)]);   // unconditional load: no per-element exec masks to keep
+        key[m] = (i < n_cand) ? kx : 0u;                   // 0 is below every trial threshold: never counted
     }
     int written = 0;
     if (kj > 0) {
@@ -55,18 +56,18 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a) {
             const uint32_t trial = thr | (1u << bit);
             int c = 0;
 #pragma unroll
-            for (int m = 0; m < PER_LANE; ++m) c += (m * 64 + lane < n_cand && key[m] >= trial) ? 1 : 0;
+            for (int m = 0; m < PER_LANE; ++m) c += (key[m] >= trial) ? 1 : 0;   // trial >= 1: padding keys stay out
             if (wave_sum(c) >= kj) thr = trial;
         }
         int above = 0;
 #pragma unroll
-        for (int m = 0; m < PER_LANE; ++m) above += (m * 64 + lane < n_cand && key[m] > thr) ? 1 : 0;
+        for (int m = 0; m < PER_LANE; ++m) above += (key[m] > thr) ? 1 : 0;
         int ties_left = kj - wave_sum(above);          // >= 1 by construction of thr
 #pragma unroll
         for (int m = 0; m < PER_LANE; ++m) {
             if (m * 64 >= n_cand) break;                // wave-uniform
             const int i = m * 64 + lane;
-            const bool valid = i < n_cand;
+            const bool valid = key[m] != 0u;            // padding keys are 0, the key of a score never is
             const bool tie = valid && key[m] == thr;
             const unsigned long long tie_mask = __ballot(tie);
             const int tie_rank = __popcll(tie_mask & ((1ull << lane) - 1ull));
@@ -75,6 +76,7 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a) {
             if (take) out[written + __popcll(take_mask & ((1ull << lane) - 1ull))] = i;
             written += __popcll(take_mask);
             ties_left -= min(ties_left, (int)__popcll(tie_mask));
+            __builtin_amdgcn_sched_barrier(0);          // keeps the ballot masks of one step from piling up in SGPRs
         }
     }
     // local blocks then the segment's own blocks
@@ -83,6 +85,88 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a) {
     const int total = written + fixed;
     for (int x = total + lane; x < a.list_len; x += 64) out[x] = -1;
     if (lane == 0) a.cnt[row] = total;
+}
+
+
+// Rows longer than 4096 blocks: one 256-thread workgroup per row, thread t owns blocks t, t+256, ...; the same
+// radix search with the wave counts added up through LDS, and a compaction whose prefix runs over the four waves.
+constexpr int kWideThreads = 256, kWidePerThread = 32;       // 8192 blocks
+__global__ __launch_bounds__(kWideThreads) void select_wide_kernel(SelectArgs a) {
+    __shared__ int part[2][4];                             // double-buffered per-wave partial counts
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const long long row = blockIdx.x;
+    const int j = (int)(row % a.n1);
+    const int diag_lo = j * a.r;
+    const int diag_hi = min(a.n2, diag_lo + a.r);
+    const int n_local = min(a.local, diag_lo);
+    const int n_cand = diag_lo - n_local;
+    const int kj = min(a.budget, n_cand);
+    const float* s = a.scores + row * a.n2;
+    int32_t* out = a.idx + row * a.list_len;
+
+    uint32_t key[kWidePerThread];
+#pragma unroll
+    for (int m = 0; m < kWidePerThread; ++m) {
+        const int i = m * kWideThreads + tid;
+        const uint32_t kx = ordered_key(s[min(i, a.n2 - 1)]);
+        key[m] = (i < n_cand) ? kx : 0u;                   // 0 is below every trial threshold: never counted
+    }
+    int step = 0;
+    auto block_sum = [&](int v) {                          // same value in every thread; one barrier per call
+        v = wave_sum(v);
+        if (lane == 0) part[step & 1][wave] = v;
+        __syncthreads();
+        const int t = part[step & 1][0] + part[step & 1][1] + part[step & 1][2] + part[step & 1][3];
+        ++step;
+        return t;
+    };
+    int written = 0;
+    if (kj > 0) {                                          // uniform over the workgroup
+        uint32_t thr = 0;
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t trial = thr | (1u << bit);
+            int c = 0;
+#pragma unroll
+            for (int m = 0; m < kWidePerThread; ++m) c += (key[m] >= trial) ? 1 : 0;
+            if (block_sum(c) >= kj) thr = trial;
+        }
+        int above = 0;
+#pragma unroll
+        for (int m = 0; m < kWidePerThread; ++m) above += (key[m] > thr) ? 1 : 0;
+        int ties_left = kj - block_sum(above);             // >= 1 by construction of thr
+#pragma unroll
+        for (int m = 0; m < kWidePerThread; ++m) {
+            if (m * kWideThreads >= n_cand) break;          // uniform
+            const int i = m * kWideThreads + tid;
+            const bool valid = key[m] != 0u;
+            const bool tie = valid && key[m] == thr;
+            // ties before this thread in index order: earlier waves of this step, then earlier lanes
+            const unsigned long long tie_mask = __ballot(tie);
+            const int tie_w = (int)__popcll(tie_mask);
+            if (lane == 0) part[step & 1][wave] = tie_w;
+            __syncthreads();
+            int tie_before = 0, tie_all = 0;
+            for (int w = 0; w < 4; ++w) { const int x = part[step & 1][w]; tie_all += x; if (w < wave) tie_before += x; }
+            ++step;
+            const int tie_rank = tie_before + (int)__popcll(tie_mask & ((1ull << lane) - 1ull));
+            const bool take = valid && (key[m] > thr || (tie && tie_rank < ties_left));
+            const unsigned long long take_mask = __ballot(take);
+            if (lane == 0) part[step & 1][wave] = (int)__popcll(take_mask);
+            __syncthreads();
+            int take_before = 0, take_all = 0;
+            for (int w = 0; w < 4; ++w) { const int x = part[step & 1][w]; take_all += x; if (w < wave) take_before += x; }
+            ++step;
+            if (take) out[written + take_before + (int)__popcll(take_mask & ((1ull << lane) - 1ull))] = i;
+            written += take_all;
+            ties_left -= min(ties_left, tie_all);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    const int fixed = diag_hi - n_cand;
+    for (int x = tid; x < fixed; x += kWideThreads) out[written + x] = n_cand + x;
+    const int total = written + fixed;
+    for (int x = total + tid; x < a.list_len; x += kWideThreads) out[x] = -1;
+    if (tid == 0) a.cnt[row] = total;
 }
 
 }  // namespace
@@ -95,7 +179,11 @@ hipError_t launch_select(const Shape& sh, const float* scores, int32_t* idx, int
     const unsigned grid = (unsigned)((a.rows + 3) / 4);
     if (sh.n2 <= 64 * 8) hipLaunchKernelGGL(select_kernel<8>, dim3(grid), dim3(256), 0, st, a);
     else if (sh.n2 <= 64 * 32) hipLaunchKernelGGL(select_kernel<32>, dim3(grid), dim3(256), 0, st, a);
-    else hipLaunchKernelGGL(select_kernel<128>, dim3(grid), dim3(256), 0, st, a);
+    else if (sh.n2 <= 64 * 64) hipLaunchKernelGGL(select_kernel<64>, dim3(grid), dim3(256), 0, st, a);
+    else {
+        if (a.rows > 0x7fffffffLL || sh.n2 > kWideThreads * kWidePerThread) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(select_wide_kernel, dim3((unsigned)a.rows), dim3(kWideThreads), 0, st, a);
+    }
     return hipGetLastError();
 }
 

@@ -87,6 +87,22 @@ def test_select_negative_and_large_budget():
     H.check_selection(Sd, idx_o, cnt_o, idx_g, cnt_g, w, exact=True)
 
 
+@pytest.mark.parametrize("n_blocks,budget", [(4096, 32), (8192, 100)])
+def test_select_long_rows_with_ties(n_blocks, budget):
+    """Rows of 4096 blocks (64 per lane) and 8192 blocks (one workgroup per row), scores quantised to a handful of
+    levels so that the k-th score is shared by hundreds of blocks and the smallest-index tie rule decides."""
+    b = 16
+    w = H.small_workload("long", 1, 2, 1, n_blocks * b, 512, b, budget, 2)
+    g = np.random.default_rng(n_blocks)
+    Sd = (g.integers(0, 7, size=(1, 2, w.n_segments, w.n_blocks)) / 8.0).astype(np.float32)
+    Sd[:, :, :, 5::11] += g.random(Sd[:, :, :, 5::11].shape, dtype=np.float32) * 1e-3     # a few distinct values too
+    idx_o, cnt_o = O.select(Sd, w.segment_size, w.block_size, w.budget_blocks, w.local_blocks)
+    q = torch.empty((1, 2, w.seq_len, 128), dtype=torch.bfloat16, device=DEV)
+    k = torch.empty((1, 1, w.seq_len, 128), dtype=torch.bfloat16, device=DEV)
+    idx_g, cnt_g = H.gpu_select(w, q, k, torch.from_numpy(Sd).to(DEV))
+    H.check_selection(Sd, idx_o, cnt_o, idx_g, cnt_g, w, exact=True)
+
+
 @pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
 def test_estimate_then_select_tie_band(case):
     w, q, k, v = make(case)
