@@ -330,18 +330,37 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
     // group ahead of their use, so that an MFMA does not wait a full LDS round trip.  The first group of a
     // matrix phase is issued before the softmax phase that precedes it.
     bf16x8 fr[2][4];
-    auto read_kg = [&](int slot, int gq, int grp) {          // K group gq: ks = 2*gq, 2*gq+1, both key halves
+    // The read addresses carry the ring slot they point into (ka: the K slot, va: the V slot) and are moved on by
+    // one slot per tile step, so that a fragment read needs no address arithmetic, only an immediate offset.
+    unsigned ka[8], va[4];
+    int ka_slot = 0, va_slot = 0;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) ka[ks] = k_base ^ (ks << 5);
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) va[dt] = v_addr[dt];
+    auto next_k_slot = [&]() {
+        const unsigned d = ka_slot == NBUF - 1 ? (unsigned)(-(NBUF - 1) * kTileBytes) : (unsigned)kTileBytes;
+        ka_slot = (ka_slot + 1) & (NBUF - 1);
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) ka[ks] += d;
+    };
+    auto next_v_slot = [&]() {
+        const unsigned d = va_slot == NBUF - 1 ? (unsigned)(-(NBUF - 1) * kTileBytes) : (unsigned)kTileBytes;
+        va_slot = (va_slot + 1) & (NBUF - 1);
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) va[dt] += d;
+    };
+    auto read_kg = [&](int gq, int grp) {                    // K group gq: ks = 2*gq, 2*gq+1, both key halves
 #pragma unroll
         for (int x = 0; x < 2; ++x)
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
-                fr[grp][2 * x + kt] =
-                    as_bf16x8(*LDS_PTR(const u32x4, (k_base ^ ((2 * gq + x) << 5)) + slot * kTileBytes + kt * 32 * 256));
+                fr[grp][2 * x + kt] = as_bf16x8(*LDS_PTR(const u32x4, ka[2 * gq + x] + kt * 32 * 256));
     };
-    auto read_vg = [&](int slot, int t4, int grp) {          // V group t4: 16 keys, all four channel tiles
+    auto read_vg = [&](int t4, int grp) {                    // V group t4: 16 keys, all four channel tiles
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) {
-            const unsigned ad = v_addr[dt] + slot * kTileBytes + t4 * 16 * 256;
+            const unsigned ad = va[dt] + t4 * 16 * 256;
             const v4bf16_lds lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(v4bf16_lds, ad));
             const v4bf16_lds hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(v4bf16_lds, ad + 8 * 256));
 #pragma unroll
@@ -366,32 +385,32 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
     };
-    auto qk = [&](int slot, f32x16 (&s)[2]) {                // S^T = K Q^T; K group 0 already on its way into fr[0]
+    auto qk = [&](f32x16 (&s)[2]) {                // S^T = K Q^T; K group 0 already on its way into fr[0]
         zero_s(s);
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
-            if (gq + 1 < 4) read_kg(slot, gq + 1, (gq + 1) & 1);
+            if (gq + 1 < 4) read_kg(gq + 1, (gq + 1) & 1);
             mfma_kg(gq, gq & 1, s);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-    auto pv = [&](int slot, const bf16x8 (&pf)[4]) {         // O^T += V^T P^T; V group 0 already on its way into fr[0]
+    auto pv = [&](const bf16x8 (&pf)[4]) {         // O^T += V^T P^T; V group 0 already on its way into fr[0]
 #pragma unroll
         for (int t4 = 0; t4 < 4; ++t4) {
-            if (t4 + 1 < 4) read_vg(slot, t4 + 1, (t4 + 1) & 1);
+            if (t4 + 1 < 4) read_vg(t4 + 1, (t4 + 1) & 1);
             mfma_vg(t4, t4 & 1, pf);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
     // PV of one tile interleaved with QK of the next; V group 0 already on its way into fr[0]
-    auto mm_both = [&](int vslot, int kslot, f32x16 (&s)[2], const bf16x8 (&pf)[4]) {
+    auto mm_both = [&](f32x16 (&s)[2], const bf16x8 (&pf)[4]) {
         zero_s(s);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            read_kg(kslot, i, 1);
+            read_kg(i, 1);
             mfma_vg(i, 0, pf);
             __builtin_amdgcn_sched_barrier(0);
-            if (i + 1 < 4) read_vg(vslot, i + 1, 0);
+            if (i + 1 < 4) read_vg(i + 1, 0);
             mfma_kg(i, 1, s);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -422,10 +441,13 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
     };
     // S^T tile -> P^T fragments; running max / sum; O rescaled when any row's max moved
     auto sm = [&](f32x16 (&s)[2], bf16x8 (&pf)[4]) {
-        float mx = fmaxf(s[0][0], s[1][0]);
+        float mx = fmaxf(s[0][0], s[0][1]), my = fmaxf(s[1][0], s[1][1]);   // two chains of v_max3
 #pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s[0][r], s[1][r]));
-        mx = half_max(mx);
+        for (int r = 2; r < 16; r += 2) {
+            mx = fmaxf(fmaxf(s[0][r], s[0][r + 1]), mx);
+            my = fmaxf(fmaxf(s[1][r], s[1][r + 1]), my);
+        }
+        mx = half_max(fmaxf(mx, my));
         const float m_new = fmaxf(m_run, mx);
         const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
         const float alpha = __builtin_amdgcn_exp2f((m_run - m_safe) * c);
@@ -502,45 +524,53 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
 
     f32x16 s[2]; bf16x8 pf[4];
     if (!rotated) {
+        // step t: ka points into the slot of K(t), va into the slot of V(t-1)
         bool have_p = false;                                         // P^T of tile t-1 waits for its PV
         bool act = ntiles > 0 && tile_active(0, nb[0]);              // wave-uniform; once false it stays false
-        if (act) read_kg(0, 0, 0);
+        va_slot = NBUF - 1;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) va[dt] += (NBUF - 1) * kTileBytes;
+        if (act) read_kg(0, 0);
         for (int t = 0; t < ntiles; ++t) {
-            const int slot = t & 3, pslot = (t - 1) & 3, nslot = (t + 1) & 3;
+            const int slot = t & 3, nslot = (t + 1) & 3;
             issue_v((t + 2) & 3, false);
             issue_k((t + 3) & 3);
             __builtin_amdgcn_s_setprio(3);                               // matrix phase: its MFMAs go ahead of the partner's VALU work
-            if (have_p && act) mm_both(pslot, slot, s, pf);
-            else if (act) qk(slot, s);
-            else if (have_p) pv(pslot, pf);
+            if (have_p && act) mm_both(s, pf);
+            else if (act) qk(s);
+            else if (have_p) pv(pf);
             __builtin_amdgcn_s_setprio(0);
+            next_k_slot(); next_v_slot();                                // K(t+1), V(t)
             const bool act_next = act && (t + 1 < ntiles) && tile_active(nslot, nb[1]);
             if (act) {
-                read_vg(slot, 0, 0);                                 // first group of the next matrix phase
+                read_vg(0, 0);                                       // first group of the next matrix phase
                 mask_if_needed(s, slot, nb[0]);
                 sm(s, pf);
             }
             have_p = act; act = act_next;
             step_end(slot);
         }
-        if (have_p) pv((ntiles - 1) & 3, pf);
+        if (have_p) pv(pf);
     } else {
+        // step t: va points into the slot of V(t), ka into the slot of K(t+1)
         bool have_s = ntiles > 0 && tile_active(0, nb[0]);
-        if (have_s) { read_kg(0, 0, 0); qk(0, s); }
+        if (have_s) { read_kg(0, 0); qk(s); }
+        next_k_slot();
         for (int t = 0; t < ntiles; ++t) {
             const int slot = t & 3, nslot = (t + 1) & 3;
             issue_v((t + 2) & 3, false);
             issue_k((t + 3) & 3);
             const bool act_next = have_s && (t + 1 < ntiles) && tile_active(nslot, nb[1]);
             if (have_s) {
-                read_vg(slot, 0, 0);                                 // first group of the matrix phase below
+                read_vg(0, 0);                                       // first group of the matrix phase below
                 mask_if_needed(s, slot, nb[0]);
                 sm(s, pf);
                 __builtin_amdgcn_s_setprio(3);
-                if (act_next) mm_both(slot, nslot, s, pf);
-                else pv(slot, pf);
+                if (act_next) mm_both(s, pf);
+                else pv(pf);
                 __builtin_amdgcn_s_setprio(0);
             }
+            next_k_slot(); next_v_slot();
             have_s = act_next;
             step_end(slot);
         }
