@@ -533,13 +533,13 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
         if (act) read_kg(0, 0);
         for (int t = 0; t < ntiles; ++t) {
             const int slot = t & 3, nslot = (t + 1) & 3;
-            issue_v((t + 2) & 3, false);
-            issue_k((t + 3) & 3);
             __builtin_amdgcn_s_setprio(3);                               // matrix phase: its MFMAs go ahead of the partner's VALU work
             if (have_p && act) mm_both(s, pf);
             else if (act) qk(s);
             else if (have_p) pv(pf);
             __builtin_amdgcn_s_setprio(0);
+            issue_v((t + 2) & 3, false);                                 // after the matrix phase: it starts with the step
+            issue_k((t + 3) & 3);
             next_k_slot(); next_v_slot();                                // K(t+1), V(t)
             const bool act_next = act && (t + 1 < ntiles) && tile_active(nslot, nb[1]);
             if (act) {
