@@ -42,8 +42,8 @@ def read_traffic(workload: str):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c3_llama3_8b_128k")
     ap.add_argument("--dense-steps", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -106,6 +106,7 @@ def main() -> int:
     est_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
     sel_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
     att_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in evs]))
+    layer_ms = np.array([e[0].elapsed_time(e[3]) for e in evs])      # per step, HIP events on the launch stream
 
     # algorithmic work of the sparse attention: 4*d flop per visited (query, key <= query) pair
     d, s, b, r, n = w.head_dim, w.segment_size, w.block_size, w.blocks_per_segment, w.seq_len
@@ -146,6 +147,7 @@ def main() -> int:
         "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": d, "seq_len": n, "segment": s, "block": b, "budget_blocks": w.budget_blocks,
                    "local_blocks": w.local_blocks},
+        "layer_ms_p10_p50_p90": [round(float(np.percentile(layer_ms, q)), 4) for q in (10, 50, 90)],
         "breakdown_ms": {"estimate": round(est_ms, 4), "select": round(sel_ms, 4), "sparse_attn": round(att_ms, 4),
                          "dense_causal_attn": round(dense_ms, 3)},
         "speedup_vs_dense": round(dense_ms / ms_per_step, 3),

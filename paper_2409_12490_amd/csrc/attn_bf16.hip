@@ -180,39 +180,27 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
         }
     }
 
-    // ---- tile loader: a wave fills rows 4*w .. 4*w+3 and 32 + 4*w .. +3 of K and of V (4 instructions) ----
+    // ---- tile loader: wave w fills rows 4*w .. 4*w+3 and 32 + 4*w .. +3 of K and of V (4 instructions) ----
     const int r4 = lane >> 4;                                // row inside the wave's 4-row group
     const int pch = lane & 15;                               // physical chunk the lane's 16 bytes land in
     const int kch = pch ^ ((4 * wave + r4) & 15);            // K: logical chunk, swizzle = row & 15
     const int vch = pch ^ (4 * r4);                          // V: logical chunk, swizzle = 4 * (row & 3)
     const unsigned tok_bytes = (unsigned)a.ks2 * 2u;         // host checks n * tok_bytes < 2^32, both < 2^24
     // byte offsets (from kp / vp) of the lane's chunks: koff/voff = the tile described last; V is issued one
-    // step later than K, so its offsets wait in voff_issue
-    // MODE 1/2: waves 0-3 also fill the rows of waves 4-7 (16 rows further down: same swizzle), which then issue
-    // no loads at all - the matrix-first waves 0-3 reach the tile barrier earlier than their partners otherwise.
-    constexpr bool SPLIT = FAST;
-    const bool loader = !SPLIT || wave < 4;
+    // step later than K, so its offsets wait in voff_issue.  Both wave roles issue their loads right after their
+    // matrix phase.
     unsigned koff[2], voff[2], voff_issue[2];
-    unsigned koff2[2], voff2[2], voff2_issue[2];             // SPLIT: the rows taken over from wave + 4
     auto issue_k = [&](int slot) {
-        if (!loader) return;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            dma16(kp, koff[i], lds0 + kKOff + slot * kTileBytes + (32 * i + 4 * wave) * 256);
-            if (SPLIT) dma16(kp, koff2[i], lds0 + kKOff + slot * kTileBytes + (32 * i + 4 * wave + 16) * 256);
-        }
+        for (int i = 0; i < 2; ++i) dma16(kp, koff[i], lds0 + kKOff + slot * kTileBytes + (32 * i + 4 * wave) * 256);
     };
     auto issue_v = [&](int slot, bool first) {               // first: straight from voff (prologue), else from voff_issue
-        if (!loader) return;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < 2; ++i)
             dma16(vp, first ? voff[i] : voff_issue[i], lds0 + kVOff + slot * kTileBytes + (32 * i + 4 * wave) * 256);
-            if (SPLIT) dma16(vp, first ? voff2[i] : voff2_issue[i], lds0 + kVOff + slot * kTileBytes + (32 * i + 4 * wave + 16) * 256);
-        }
     };
-    auto dma_wait = [&]() {                                  // all but the loads of the newest tile pair have landed
-        if (SPLIT) { if (loader) asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); }
-        else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    auto dma_wait = [&]() {                                  // all but the 4 loads of the newest tile pair have landed
+        asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
     };
 
     // MODE 0 state: the list is walked incrementally per lane row: (e, off) = (entry, offset inside the
@@ -278,27 +266,23 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 koff[i] = sb + lane_k[i]; voff[i] = sb + lane_v[i];
-                koff2[i] = koff[i] + 16 * tok_bytes; voff2[i] = voff[i] + 16 * tok_bytes;
             }
         } else {                                             // ragged last tile or no tile: invalid rows read token 0
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 const int tok = base + 32 * i + 4 * wave + r4;
-                const bool valid = base >= 0 && tok < a.n, valid2 = base >= 0 && tok + 16 < a.n;
+                const bool valid = base >= 0 && tok < a.n;
                 const unsigned sb = __umul24(valid ? (unsigned)tok : 0u, tok_bytes);
-                const unsigned sb2 = __umul24(valid2 ? (unsigned)tok + 16u : 0u, tok_bytes);
                 koff[i] = sb + kch * 16; voff[i] = sb + vch * 16;
-                koff2[i] = sb2 + kch * 16; voff2[i] = sb2 + vch * 16;
             }
         }
     };
     // describe the next tile in order (its DMA offsets go to koff/voff); MODE 0 also publishes its row tokens
     auto describe_next = [&](int slot) {
         voff_issue[0] = voff[0]; voff_issue[1] = voff[1];
-        if (SPLIT) { voff2_issue[0] = voff2[0]; voff2_issue[1] = voff2[1]; }
         if (FAST) {
             nb[0] = nb[1]; nb[1] = nb[2]; nb[2] = nb[3]; nb[3] = next_base();
-            if (loader) base_offsets(nb[3]);
+            base_offsets(nb[3]);
         } else {
             tile_offsets(); put_tok(slot); fetch_entries();
         }
@@ -512,7 +496,6 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
             if (s3 == 1 || s3 == 2) {
                 if (s3 == 2) { issue_v(1, false); issue_k(2); }
                 voff_issue[0] = voff[0]; voff_issue[1] = voff[1];
-                if (SPLIT) { voff2_issue[0] = voff2[0]; voff2_issue[1] = voff2[1]; }
             }
         }
     }
@@ -538,7 +521,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
             else if (act) qk(s);
             else if (have_p) pv(pf);
             __builtin_amdgcn_s_setprio(0);
-            issue_v((t + 2) & 3, false);                                 // after the matrix phase: it starts with the step
+            issue_v((t + 2) & 3, false);                                 // after the matrix phase, which starts with the step
             issue_k((t + 3) & 3);
             next_k_slot(); next_v_slot();                                // K(t+1), V(t)
             const bool act_next = act && (t + 1 < ntiles) && tile_active(nslot, nb[1]);
@@ -558,8 +541,6 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
         next_k_slot();
         for (int t = 0; t < ntiles; ++t) {
             const int slot = t & 3, nslot = (t + 1) & 3;
-            issue_v((t + 2) & 3, false);
-            issue_k((t + 3) & 3);
             const bool act_next = have_s && (t + 1 < ntiles) && tile_active(nslot, nb[1]);
             if (have_s) {
                 read_vg(0, 0);                                       // first group of the matrix phase below
@@ -570,6 +551,8 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
                 else pv(pf);
                 __builtin_amdgcn_s_setprio(0);
             }
+            issue_v((t + 2) & 3, false);                                 // after the matrix phase, like waves 0-3
+            issue_k((t + 3) & 3);
             next_k_slot(); next_v_slot();
             have_s = act_next;
             step_end(slot);
