@@ -63,7 +63,8 @@ typedef struct critiprefill_params {
 /* Length of one block list: budget_blocks + local_blocks + r. */
 int32_t critiprefill_list_len(const critiprefill_params *p);
 
-/* Bytes of scratch critiprefill_estimate needs (the max/min representatives of Algorithm 1). */
+/* Bytes of scratch critiprefill_estimate needs (the max/min representatives of Algorithm 1 and, for bf16,
+ * the per-chunk softmax statistics of the score step). */
 size_t critiprefill_workspace_bytes(const critiprefill_params *p);
 
 /*

@@ -64,13 +64,16 @@ int check_attn(const cp::Shape& sh, const void* q, const void* k, const void* v,
     return CP_OK;
 }
 
-size_t rep_bytes(const cp::Shape& sh, size_t* krep_offset) {
+// workspace of critiprefill_estimate: [Q representatives | K representatives | score statistics]
+size_t workspace_layout(const cp::Shape& sh, size_t* krep_offset, size_t* stats_offset) {
     const size_t esz = sh.dtype == CP_DTYPE_BF16 ? 2 : 4;
     size_t qb = (size_t)sh.batch * sh.hq * sh.n1 * 2 * cp::kHeadDim * esz;
     qb = (qb + 255) & ~(size_t)255;
-    const size_t kb = (size_t)sh.batch * sh.hkv * sh.n2 * 2 * cp::kHeadDim * esz;
+    size_t kb = (size_t)sh.batch * sh.hkv * sh.n2 * 2 * cp::kHeadDim * esz;
+    kb = (kb + 255) & ~(size_t)255;
     if (krep_offset) *krep_offset = qb;
-    return qb + kb;
+    if (stats_offset) *stats_offset = qb + kb;
+    return qb + kb + cp::score_stats_bytes(sh);
 }
 
 }  // namespace
@@ -86,7 +89,7 @@ int32_t critiprefill_list_len(const critiprefill_params* p) {
 size_t critiprefill_workspace_bytes(const critiprefill_params* p) {
     cp::Shape sh;
     if (make_shape(p, &sh) != CP_OK) return 0;
-    return rep_bytes(sh, nullptr);
+    return workspace_layout(sh, nullptr, nullptr);
 }
 
 int critiprefill_estimate(const critiprefill_params* p, const void* q, const void* k, const float* prev_scores,
@@ -101,13 +104,14 @@ int critiprefill_estimate(const critiprefill_params* p, const void* q, const voi
         return CP_ERR_ALIGN;
     if ((e = check_strides(sh.qs, cp::kHeadDim)) != CP_OK) return e;
     if ((e = check_strides(sh.kvs, cp::kHeadDim)) != CP_OK) return e;
-    size_t koff = 0;
-    if (workspace_bytes < rep_bytes(sh, &koff)) return CP_ERR_WORKSPACE;
+    size_t koff = 0, soff = 0;
+    if (workspace_bytes < workspace_layout(sh, &koff, &soff)) return CP_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)hip_stream;
     void* qrep = workspace;
     void* krep = (char*)workspace + koff;
     if (cp::launch_pool(sh, q, k, qrep, krep, st) != hipSuccess) return CP_ERR_LAUNCH;
-    if (cp::launch_score(sh, qrep, krep, prev_scores, scores, st) != hipSuccess) return CP_ERR_LAUNCH;
+    float* stats = (float*)((char*)workspace + soff);
+    if (cp::launch_score(sh, qrep, krep, prev_scores, scores, stats, st) != hipSuccess) return CP_ERR_LAUNCH;
     return CP_OK;
 }
 

@@ -140,9 +140,14 @@ __global__ __launch_bounds__(256) void pool_fp32_kernel(PoolArgs a) {
 // ---------------------------------------------------------------------------------------------
 struct ScoreArgs {
     const void* qrep; const void* krep; const float* prev; float* scores;
+    float* stats;                          // bf16 path: per-chunk softmax statistics (see score_stats_kernel)
     int hq, hkv, n1, n2, r, domain;
+    int nchunk, n1_pad;
     float scale, alpha;
 };
+constexpr int kScoreWaves = 8;             // waves per workgroup of the bf16 score kernels, 16 segments each
+constexpr int kScoreSegPerWg = 16 * kScoreWaves;
+constexpr int kScoreChunk = 128;           // blocks per workgroup (64 KiB of representatives in LDS)
 
 __device__ __forceinline__ float block_reduce_max(float v, float* red) {
     for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
@@ -251,158 +256,312 @@ __global__ __launch_bounds__(256) void score_valu_kernel(ScoreArgs a) {
 
 
 // ---------------------------------------------------------------------------------------------
-// score, bf16: the four representative products as one bf16 MFMA GEMM (representatives are exact
-// bf16 values, so every product is exact and only the fp32 accumulation rounds).
+// score, bf16: the four representative products as bf16 MFMA GEMMs (representatives are exact bf16
+// values, so every product is exact and only the fp32 accumulation rounds).
 //
-// Workgroup = 4 waves = 16 segments of one (batch, head).  A operand (32 rows) = [Q_max of the 16
-// segments ; Q_min of the 16 segments], kept in registers.  B operand = 32 blocks of K_max, then the same
-// 32 blocks of K_min, read straight from global memory (1 MiB per KV head, L2 resident).  In the 32x32
-// result a lane holds, for its block column, both query representatives of 8 segments; with the two
-// MFMA results that is all of S1..S4 for 8 (segment, block) pairs in one lane.  Wave w takes the block
-// tiles w, w+4, ...  Pass 1 finds every row's max and sum of exponentials (online, per lane, then
-// reduced over lanes and waves); pass 2 recomputes the products and writes the combined score.
+// The blocks of a (batch, head) are cut into chunks of 128; a workgroup = 8 waves takes one chunk and 128
+// segments, wave w the segments 16w .. 16w+15.  Z^T = K_rep . Q_rep^T: the A operand is a tile of 32 blocks
+// of K_max (then K_min); the chunk's representatives (64 KiB) go global -> LDS once for all eight waves, all
+// loads issued up front (global_load_lds, no register staging), two workgroups per compute unit so that one
+// computes while the other loads; the B operand, column n = (segment n >> 1, representative n & 1), stays in
+// registers.  A lane then holds, for its column, 16 blocks of the tile in registers: the softmax
+// statistics over blocks are in-lane reductions plus one exchange between the wave halves, and the two
+// query representatives of a segment sit in neighbouring lanes (one DPP exchange per score).
+//
+//   score_stats_kernel   per chunk and column: max and sum of 2^(c z - max) of the two products  -> stats
+//   score_write_kernel   merges the chunk statistics, recomputes the products of its chunk, normalises,
+//                        combines (S1+S3)/2 vs (S2+S4)/2, masks, fuses, stores.  Chunks that lie wholly
+//                        after every segment of the workgroup are written without any product.
 // ---------------------------------------------------------------------------------------------
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+#define SCORE_LDS(T, off) ((__attribute__((address_space(3))) T*)(uintptr_t)(off))
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) {
     union { uint4 u; bf16x8 b; } c; c.u = v; return c.b;
 }
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
+    union { u32x4 u; bf16x8 b; } c; c.u = v; return c.b;
+}
+__device__ __forceinline__ float halves_max(float x) {     // max over lanes l and l ^ 32
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float halves_sum(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float neighbour(float x) {      // the value of lane l ^ 1
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xF, 0xF, true));
+}
 
-constexpr int kSegPerWg = 16;
+struct ScoreTile {
+    static constexpr int kTileBlocks = 32;                  // blocks per MFMA tile
+    static constexpr int kTileBytes = kTileBlocks * 2 * kHeadDim * 2;   // max row + min row per block, bf16
+};
 
-__global__ __launch_bounds__(256) void score_mfma_kernel(ScoreArgs a) {
-    __shared__ float red_m[4][2][2][kSegPerWg];   // [wave][a][bb][segment]
-    __shared__ float red_l[4][2][2][kSegPerWg];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int l32 = lane & 31, hh = lane >> 5;
-    const int j0 = blockIdx.x * kSegPerWg, h = blockIdx.y, bb_ = blockIdx.z;
-    const int g = h / (a.hq / a.hkv);
-    const long long qrow0 = ((long long)bb_ * a.hq + h) * a.n1;
-    const long long kbase = ((long long)bb_ * a.hkv + g) * a.n2;
-    constexpr float kLog2e = 1.4426950408889634f;
-    const float c = a.scale * kLog2e;                        // logits in log2 units
-
-    // A fragments: row m = l32 -> representative (m >> 4) of segment j0 + (m & 15)
+// The part both kernels share: the workgroup's coordinates, the B operand, the staged A tiles.
+struct ScoreCtx {
+    int lane, wave, l32, hh;
+    int chunk, j0, seg, rep, h, bb_;
+    int i_begin, i_end, ntile;                              // blocks of the chunk, tiles of 32
+    long long qrow0;                                        // row of segment 0 of this (batch, head) in scores
+    const uint16_t* ksrc;                                   // K representatives of block 0 of this KV head
+    int vis;                                                // first block wholly after the lane's segment
+    int vis_wg;                                             // ... after the last segment of the workgroup
+    int vis_wave, vis_wave_max;                             // ... after the first / last segment of the wave
     bf16x8 qf[8];
-    {
-        const int jq = min(j0 + (l32 & 15), a.n1 - 1);
-        const uint16_t* src = (const uint16_t*)a.qrep + ((qrow0 + jq) * 2 + (l32 >> 4)) * kHeadDim + 8 * hh;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qf[ks] = as_bf16x8(*(const uint4*)(src + 16 * ks));
-    }
-    // the lane's 8 segments: register r of an accumulator is row 8*(r>>2) + 4*hh + (r&3)
-    //   representative = r >> 3, segment slot x = ((r >> 2) & 1) * 4 + (r & 3) -> segment j0 + 8*((r>>2)&1) + 4*hh + (r&3)
-    int vis[8];                                             // first block wholly after the segment
-#pragma unroll
-    for (int x = 0; x < 8; ++x) {
-        const int j = j0 + 8 * (x >> 2) + 4 * hh + (x & 3);
-        vis[x] = min(a.n2, (j + 1) * a.r);
-    }
-    const int ntile = (a.n2 + 31) / 32;
+    unsigned lds0;
+};
 
-    // Z for one 32-block tile: z[bb][r]
-    auto tile_z = [&](int nt, f32x16 (&z)[2]) {
-        const int i = min(nt * 32 + l32, a.n2 - 1);
-        const uint16_t* src = (const uint16_t*)a.krep + (kbase + i) * 2 * kHeadDim + 8 * hh;
+__device__ __forceinline__ void score_setup(const ScoreArgs& a, ScoreCtx& c, unsigned lds0) {
+    const int tid = threadIdx.x;
+    c.lane = tid & 63; c.wave = tid >> 6; c.l32 = c.lane & 31; c.hh = c.lane >> 5;
+    c.chunk = blockIdx.x; c.j0 = blockIdx.y * kScoreSegPerWg + 16 * c.wave;
+    c.h = blockIdx.z % a.hq; c.bb_ = blockIdx.z / a.hq;
+    c.seg = c.j0 + (c.l32 >> 1); c.rep = c.l32 & 1;
+    c.i_begin = c.chunk * kScoreChunk; c.i_end = min(a.n2, c.i_begin + kScoreChunk);
+    c.ntile = (c.i_end - c.i_begin + ScoreTile::kTileBlocks - 1) / ScoreTile::kTileBlocks;
+    c.qrow0 = ((long long)c.bb_ * a.hq + c.h) * a.n1;
+    const int g = c.h / (a.hq / a.hkv);
+    c.ksrc = (const uint16_t*)a.krep + ((long long)c.bb_ * a.hkv + g) * a.n2 * 2 * kHeadDim;
+    c.vis = min(a.n2, (min(c.seg, a.n1 - 1) + 1) * a.r);
+    c.vis_wg = min(a.n2, min(a.n1, (int)(blockIdx.y + 1) * kScoreSegPerWg) * a.r);
+    c.vis_wave = min(a.n2, (min(c.j0, a.n1 - 1) + 1) * a.r);
+    c.vis_wave_max = min(a.n2, min(a.n1, c.j0 + 16) * a.r);
+    c.lds0 = lds0;
+    const uint16_t* src = (const uint16_t*)a.qrep + ((c.qrow0 + min(c.seg, a.n1 - 1)) * 2 + c.rep) * kHeadDim + 8 * c.hh;
 #pragma unroll
-        for (int b2 = 0; b2 < 2; ++b2) {
+    for (int ks = 0; ks < 8; ++ks) c.qf[ks] = as_bf16x8(*(const uint4*)(src + 16 * ks));
+}
+// The whole chunk, global -> LDS: instruction x of wave w (X instructions each) writes the 1 KiB at
+// 1024 * (X w + x) = rows 4 (X w + x) .. +3 (row = 2 * block + representative, 256 B); a lane's 16 bytes
+// land at lane * 16 inside that KiB, so the XOR swizzle of the 16-byte chunks by the block index (which spreads the 32 row reads of
+// a fragment over all banks) is applied to the global address.  Blocks past the last one repeat it.
+__device__ __forceinline__ void score_load_chunk(const ScoreArgs& a, const ScoreCtx& c) {
+    const unsigned long long pv = (unsigned long long)c.ksrc;
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)pv);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(pv >> 32));
+    const void* sbase = (const void*)(((unsigned long long)hi << 32) | lo);
+    constexpr int kPerWave = kScoreChunk / 2 / kScoreWaves;  // 1 KiB instructions per wave
 #pragma unroll
-            for (int r = 0; r < 16; ++r) z[b2][r] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                const bf16x8 kf = as_bf16x8(*(const uint4*)(src + b2 * kHeadDim + 16 * ks));
-                z[b2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[ks], kf, z[b2], 0, 0, 0);
-            }
-        }
-    };
-
-    // ---- pass 1: per lane online max / sum of 2^(c z) over its block columns -------------------
-    float m[2][16], l[2][16];
-#pragma unroll
-    for (int b2 = 0; b2 < 2; ++b2)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { m[b2][r] = -INFINITY; l[b2][r] = 0.f; }
-    for (int nt = wave; nt < ntile; nt += 4) {
-        f32x16 z[2];
-        tile_z(nt, z);
-        const int i = nt * 32 + l32;
-#pragma unroll
-        for (int b2 = 0; b2 < 2; ++b2)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int x = ((r >> 2) & 1) * 4 + (r & 3);
-                const bool in_dom = i < (a.domain == 0 ? a.n2 : vis[x]);
-                const float v = in_dom ? z[b2][r] * c : -INFINITY;
-                const float mn = fmaxf(m[b2][r], v);
-                const float ms = (mn == -INFINITY) ? 0.f : mn;
-                l[b2][r] = l[b2][r] * exp2f(m[b2][r] - ms) + exp2f(v - ms);
-                m[b2][r] = mn;
-            }
+    for (int x = 0; x < kPerWave; ++x) {
+        const int row = 4 * (kPerWave * c.wave + x) + (c.lane >> 4);
+        const int blk = min(c.i_begin + (row >> 1), a.n2 - 1);
+        const int lc = (c.lane & 15) ^ ((row >> 1) & 15);
+        const unsigned voff = (unsigned)(((blk * 2 + (row & 1)) * kHeadDim + lc * 8) * 2);
+        const unsigned dst = __builtin_amdgcn_readfirstlane(c.lds0 + 1024u * (kPerWave * c.wave + x));
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(voff), "s"(sbase)
+                     : "memory");
     }
-    // reduce over the 32 lanes of a half (block columns), then over the waves
-#pragma unroll
-    for (int b2 = 0; b2 < 2; ++b2)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            float mm = m[b2][r], ll = l[b2][r];
-#pragma unroll
-            for (int o = 16; o > 0; o >>= 1) {
-                const float m2 = __shfl_xor(mm, o), l2 = __shfl_xor(ll, o);
-                const float mn = fmaxf(mm, m2);
-                const float ms = (mn == -INFINITY) ? 0.f : mn;
-                ll = ll * exp2f(mm - ms) + l2 * exp2f(m2 - ms);
-                mm = mn;
-            }
-            if (l32 == 0) {
-                const int seg = 8 * ((r >> 2) & 1) + 4 * hh + (r & 3);
-                red_m[wave][r >> 3][b2][seg] = mm;
-                red_l[wave][r >> 3][b2][seg] = ll;
-            }
-        }
+}
+__device__ __forceinline__ void score_chunk_ready() {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    float inv[2][16];                                       // 1 / sum, and m becomes the final max
+}
+// z[b2][r] = K_rep(b2)[block 8*(r>>2) + 4*hh + (r&3) of the tile] . Q_rep[column]
+__device__ __forceinline__ void score_tile(const ScoreCtx& c, int nt, f32x16 (&z)[2]) {
+    const unsigned base = c.lds0 + nt * ScoreTile::kTileBytes + c.l32 * 512;
+    const int sw = c.l32 & 15;
 #pragma unroll
-    for (int b2 = 0; b2 < 2; ++b2)
+    for (int b2 = 0; b2 < 2; ++b2) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int seg = 8 * ((r >> 2) & 1) + 4 * hh + (r & 3);
-            float mm = -INFINITY;
+        for (int r = 0; r < 16; ++r) z[b2][r] = 0.f;
 #pragma unroll
-            for (int w = 0; w < 4; ++w) mm = fmaxf(mm, red_m[w][r >> 3][b2][seg]);
-            const float ms = (mm == -INFINITY) ? 0.f : mm;
-            float ll = 0.f;
-#pragma unroll
-            for (int w = 0; w < 4; ++w) ll += red_l[w][r >> 3][b2][seg] * exp2f(red_m[w][r >> 3][b2][seg] - ms);
-            m[b2][r] = ms;
-            inv[b2][r] = ll > 0.f ? 1.0f / ll : 0.f;
+        for (int ks = 0; ks < 8; ++ks) {
+            const bf16x8 kf = as_bf16x8(*SCORE_LDS(const u32x4, base + b2 * 256 + (((2 * ks + c.hh) ^ sw) << 4)));
+            z[b2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, c.qf[ks], z[b2], 0, 0, 0);
         }
+    }
+}
+// statistics of chunk cc, product b2, column col: stats[(((bh * nchunk + cc) * 2 + b2) * 2 + which) * cols + col]
+__device__ __forceinline__ long long stats_index(const ScoreArgs& a, const ScoreCtx& c, int cc, int b2, int which) {
+    const long long cols = 2LL * a.n1_pad;
+    return ((((long long)blockIdx.z * a.nchunk + cc) * 2 + b2) * 2 + which) * cols + 2 * c.seg + c.rep;
+}
 
-    // ---- pass 2: recompute, normalise, combine, mask, fuse, store -------------------------------
-    for (int nt = wave; nt < ntile; nt += 4) {
+__global__ __launch_bounds__(64 * kScoreWaves, 4) void score_stats_kernel(ScoreArgs a) {
+    __shared__ __attribute__((aligned(1024))) unsigned char tiles[kScoreChunk * 2 * kHeadDim * 2];
+    ScoreCtx c;
+    score_setup(a, c, (unsigned)(uintptr_t)tiles);
+    if (a.domain == 1 && c.i_begin >= c.vis_wg) return;     // uniform: no visible block for any segment here
+    constexpr float kLog2e = 1.4426950408889634f;
+    const float cs = a.scale * kLog2e;                      // logits in log2 units
+    const int dom = a.domain == 0 ? a.n2 : c.vis;
+    const int dom_wave = a.domain == 0 ? a.n2 : c.vis_wave; // blocks below it count for every column of the wave
+    float m[2] = {-INFINITY, -INFINITY}, l[2] = {0.f, 0.f};
+    score_load_chunk(a, c);
+    score_chunk_ready();
+    for (int nt = 0; nt < c.ntile; ++nt) {
         f32x16 z[2];
-        tile_z(nt, z);
-        const int i = nt * 32 + l32;
-        if (i >= a.n2) continue;
-#pragma unroll
-        for (int x = 0; x < 8; ++x) {
-            const int j = j0 + 8 * (x >> 2) + 4 * hh + (x & 3);
-            if (j >= a.n1) continue;
-            const int r0 = 4 * (x >> 2) + (x & 3), r1 = r0 + 8;   // Q_max row and Q_min row of the segment
-            const bool in_dom = i < (a.domain == 0 ? a.n2 : vis[x]);
-            float p[2][2];
+        score_tile(c, nt, z);
+        const int i0 = c.i_begin + nt * ScoreTile::kTileBlocks + 4 * c.hh;
+        if (cs > 0.f && c.i_begin + (nt + 1) * ScoreTile::kTileBlocks <= dom_wave) {
+            // every block of the tile counts for every column of the wave: no masks, the scale folded into one fma
 #pragma unroll
             for (int b2 = 0; b2 < 2; ++b2) {
-                p[0][b2] = in_dom ? exp2f(z[b2][r0] * c - m[b2][r0]) * inv[b2][r0] : 0.f;
-                p[1][b2] = in_dom ? exp2f(z[b2][r1] * c - m[b2][r1]) * inv[b2][r1] : 0.f;
+                float mt = fmaxf(z[b2][0], z[b2][1]);
+#pragma unroll
+                for (int r = 2; r < 16; r += 2) mt = fmaxf(fmaxf(z[b2][r], z[b2][r + 1]), mt);
+                mt = halves_max(mt) * cs;
+                const float mn = fmaxf(m[b2], mt);
+                float sum = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(fmaf(z[b2][r], cs, -mn));
+                l[b2] = l[b2] * __builtin_amdgcn_exp2f(m[b2] - mn) + sum;
+                m[b2] = mn;
             }
-            // S1 = (max,max), S2 = (max,min), S3 = (min,max), S4 = (min,min)
-            float sc = fmaxf((p[0][0] + p[1][0]) * 0.5f, (p[0][1] + p[1][1]) * 0.5f);
-            if (i >= vis[x]) sc = 0.f;
-            const long long off = (qrow0 + j) * a.n2 + i;
-            if (a.prev) sc = a.alpha * sc + (1.0f - a.alpha) * a.prev[off];
-            if (fabsf(sc) < 1.17549435e-38f) sc = 0.f;
-            a.scores[off] = sc;
+            continue;
+        }
+#pragma unroll
+        for (int b2 = 0; b2 < 2; ++b2) {
+            float v[16];
+            float mt = -INFINITY;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                v[r] = (i0 + 8 * (r >> 2) + (r & 3) < dom) ? z[b2][r] * cs : -INFINITY;
+                mt = fmaxf(mt, v[r]);
+            }
+            mt = halves_max(mt);
+            const float mn = fmaxf(m[b2], mt);
+            const float ms = (mn == -INFINITY) ? 0.f : mn;
+            float sum = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sum += exp2f(v[r] - ms);
+            l[b2] = l[b2] * exp2f(m[b2] - ms) + sum;        // per-half partial sums under a common max
+            m[b2] = mn;
+        }
+    }
+#pragma unroll
+    for (int b2 = 0; b2 < 2; ++b2) {
+        const float lt = halves_sum(l[b2]);
+        if (c.hh == 0) {
+            a.stats[stats_index(a, c, c.chunk, b2, 0)] = m[b2];
+            a.stats[stats_index(a, c, c.chunk, b2, 1)] = lt;
+        }
+    }
+}
+
+__global__ __launch_bounds__(64 * kScoreWaves, 4) void score_write_kernel(ScoreArgs a) {
+    __shared__ __attribute__((aligned(1024))) unsigned char tiles[kScoreChunk * 2 * kHeadDim * 2];
+    ScoreCtx c;
+    score_setup(a, c, (unsigned)(uintptr_t)tiles);
+    const bool vec = (a.n2 & 3) == 0;                       // rows of scores are 16-byte aligned
+    auto finish = [&](float sc, long long off) {            // fusion and the subnormal flush
+        if (a.prev) sc = a.alpha * sc + (1.0f - a.alpha) * a.prev[off];
+        if (fabsf(sc) < 1.17549435e-38f) sc = 0.f;
+        return sc;
+    };
+    if (c.i_begin >= c.vis_wg) {                            // uniform: nothing of this chunk is visible
+        const int width = c.i_end - c.i_begin;
+        for (int x = threadIdx.x; x < kScoreSegPerWg * width; x += 64 * kScoreWaves) {
+            const int j = blockIdx.y * kScoreSegPerWg + x / width;
+            if (j >= a.n1) break;
+            const long long off = (c.qrow0 + j) * a.n2 + c.i_begin + x % width;
+            a.scores[off] = finish(0.f, off);
+        }
+        return;
+    }
+    constexpr float kLog2e = 1.4426950408889634f;
+    const float cs = a.scale * kLog2e;
+    const int dom = a.domain == 0 ? a.n2 : c.vis;
+    score_load_chunk(a, c);                                 // the merge below runs while the chunk lands
+    // merge the chunk statistics of the lane's column: the lane does the product b2 = hh, the same column's
+    // lane in the other wave half does the other one (domain 1: chunks past the workgroup's last visible
+    // block were never written)
+    const int ncc = a.domain == 0 ? a.nchunk : (c.vis_wg + kScoreChunk - 1) / kScoreChunk;
+    float mx[2], inv[2];
+    {
+        float M = -INFINITY, L = 0.f;
+        const long long step = stats_index(a, c, 1, 0, 0) - stats_index(a, c, 0, 0, 0);
+        const float* sm_ = a.stats + stats_index(a, c, 0, c.hh, 0);
+        const float* sl_ = a.stats + stats_index(a, c, 0, c.hh, 1);
+#pragma unroll 4
+        for (int cc = 0; cc < ncc; ++cc) {
+            const float mc = sm_[cc * step], lc = sl_[cc * step];
+            const float mn = fmaxf(M, mc);
+            const float ms = (mn == -INFINITY) ? 0.f : mn;
+            L = L * exp2f(M - ms) + lc * exp2f(mc - ms);
+            M = mn;
+        }
+        const float own_m = (M == -INFINITY) ? 0.f : M;
+        const float own_i = L > 0.f ? 1.0f / L : 0.f;
+        const auto rm = __builtin_amdgcn_permlane32_swap(__float_as_uint(own_m), __float_as_uint(own_m), false, false);
+        const auto ri = __builtin_amdgcn_permlane32_swap(__float_as_uint(own_i), __float_as_uint(own_i), false, false);
+        const float oth_m = __uint_as_float(c.hh ? rm[0] : rm[1]);   // the value of lane l ^ 32
+        const float oth_i = __uint_as_float(c.hh ? ri[0] : ri[1]);
+        mx[0] = c.hh ? oth_m : own_m; mx[1] = c.hh ? own_m : oth_m;
+        inv[0] = c.hh ? oth_i : own_i; inv[1] = c.hh ? own_i : oth_i;
+    }
+    // 2^(c z + fold) = 2^(c z - max) / sum / 2; usable when every column of the wave has a positive sum
+    float fold[2];
+    fold[0] = -mx[0] + __log2f(inv[0]) - 1.0f; fold[1] = -mx[1] + __log2f(inv[1]) - 1.0f;
+    const bool l_pos = __builtin_amdgcn_ballot_w64(inv[0] > 0.f && inv[1] > 0.f) == ~0ull;
+    score_chunk_ready();
+    for (int nt = 0; nt < c.ntile; ++nt) {
+        f32x16 z[2];
+        const bool unseen = c.i_begin + nt * ScoreTile::kTileBlocks >= c.vis_wave_max;   // by every segment of the wave
+        if (!unseen) score_tile(c, nt, z);
+        const int i0 = c.i_begin + nt * ScoreTile::kTileBlocks + 4 * c.hh;
+        // S1 = (max,max), S2 = (max,min), S3 = (min,max), S4 = (min,min): the lane has the products of its
+        // query representative with K_max (b2 = 0) and K_min (b2 = 1), its neighbour those of the other one
+        float sc[16];
+        const int tile_end = c.i_begin + (nt + 1) * ScoreTile::kTileBlocks;
+        if (unseen) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sc[r] = 0.f;
+        } else if (cs > 0.f && tile_end <= c.vis_wave && l_pos) {
+            // every block of the tile is visible to every segment of the wave: 1/sum and the 1/2 of the average
+            // are folded into the exponent
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(z[0][r], cs, fold[0]));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(z[1][r], cs, fold[1]));
+                sc[r] = fmaxf(p0 + neighbour(p0), p1 + neighbour(p1));
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int i = i0 + 8 * (r >> 2) + (r & 3);
+                const bool in_dom = i < dom;
+                const float p0 = in_dom ? exp2f(z[0][r] * cs - mx[0]) * inv[0] : 0.f;
+                const float p1 = in_dom ? exp2f(z[1][r] * cs - mx[1]) * inv[1] : 0.f;
+                const float t0 = p0 + neighbour(p0), t1 = p1 + neighbour(p1);
+                sc[r] = (i < c.vis) ? fmaxf(t0, t1) * 0.5f : 0.f;
+            }
+        }
+        // both lanes of a pair hold the segment's 16 scores: representative 0 stores blocks 0-7 and 16-23 of
+        // the lane half's 16, representative 1 the rest, four consecutive blocks at a time
+        if (c.seg < a.n1) {
+#pragma unroll
+            for (int g2 = 0; g2 < 2; ++g2) {
+                const int g = 2 * g2 + c.rep;               // wave-varying but only two values: both compiled
+                const int i = i0 + 8 * g;
+                const long long off = (c.qrow0 + c.seg) * a.n2 + i;
+                float w[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = c.rep ? sc[4 * (2 * g2 + 1) + e] : sc[4 * (2 * g2) + e];
+                if (vec) {
+                    if (i < a.n2) {
+                        float4 o;
+                        if (a.prev) {
+                            const float4 pv = *(const float4*)(a.prev + off);
+                            o.x = a.alpha * w[0] + (1.0f - a.alpha) * pv.x; o.y = a.alpha * w[1] + (1.0f - a.alpha) * pv.y;
+                            o.z = a.alpha * w[2] + (1.0f - a.alpha) * pv.z; o.w = a.alpha * w[3] + (1.0f - a.alpha) * pv.w;
+                        } else { o.x = w[0]; o.y = w[1]; o.z = w[2]; o.w = w[3]; }
+                        if (fabsf(o.x) < 1.17549435e-38f) o.x = 0.f;
+                        if (fabsf(o.y) < 1.17549435e-38f) o.y = 0.f;
+                        if (fabsf(o.z) < 1.17549435e-38f) o.z = 0.f;
+                        if (fabsf(o.w) < 1.17549435e-38f) o.w = 0.f;
+                        *(float4*)(a.scores + off) = o;
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (i + e < a.n2) a.scores[off + e] = finish(w[e], off + e);
+                }
+            }
         }
     }
 }
@@ -424,26 +583,38 @@ hipError_t launch_pool(const Shape& sh, const void* q, const void* k, void* qrep
     return hipGetLastError();
 }
 
+size_t score_stats_bytes(const Shape& sh) {
+    if (sh.dtype != 1) return 0;
+    const size_t nchunk = (sh.n2 + kScoreChunk - 1) / kScoreChunk;
+    const size_t n1_pad = (size_t)((sh.n1 + kScoreSegPerWg - 1) / kScoreSegPerWg) * kScoreSegPerWg;
+    return (size_t)sh.batch * sh.hq * nchunk * 2 * 2 * (2 * n1_pad) * sizeof(float);
+}
+
 hipError_t launch_score(const Shape& sh, const void* qrep, const void* krep, const float* prev, float* scores,
-                        hipStream_t st) {
+                        float* stats, hipStream_t st) {
     ScoreArgs a;
-    a.qrep = qrep; a.krep = krep; a.prev = prev; a.scores = scores;
+    a.qrep = qrep; a.krep = krep; a.prev = prev; a.scores = scores; a.stats = stats;
     a.hq = sh.hq; a.hkv = sh.hkv; a.n1 = sh.n1; a.n2 = sh.n2; a.r = sh.r; a.domain = sh.softmax_domain;
     a.scale = sh.score_scale; a.alpha = sh.alpha;
+    a.nchunk = (sh.n2 + kScoreChunk - 1) / kScoreChunk;
+    a.n1_pad = (sh.n1 + kScoreSegPerWg - 1) / kScoreSegPerWg * kScoreSegPerWg;
     if (sh.dtype == 1) {
-        dim3 grid_m((sh.n1 + kSegPerWg - 1) / kSegPerWg, sh.hq, sh.batch);
-        hipLaunchKernelGGL(score_mfma_kernel, grid_m, dim3(256), 0, st, a);
+        if ((long long)sh.batch * sh.hq > 65535) return hipErrorInvalidValue;
+        dim3 grid_m(a.nchunk, a.n1_pad / kScoreSegPerWg, sh.batch * sh.hq);
+        hipLaunchKernelGGL(score_stats_kernel, grid_m, dim3(64 * kScoreWaves), 0, st, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(score_write_kernel, grid_m, dim3(64 * kScoreWaves), 0, st, a);
         return hipGetLastError();
     }
     const size_t smem = (2 * kHeadDim + 4 + 4 * (size_t)sh.n2) * sizeof(float);
     dim3 grid(sh.n1, sh.hq, sh.batch);
-    const void* fn = sh.dtype == 1 ? (const void*)score_valu_kernel<true> : (const void*)score_valu_kernel<false>;
+    const void* fn = (const void*)score_valu_kernel<false>;
     if (smem > 48 * 1024) {
         const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
     }
-    if (sh.dtype == 1) hipLaunchKernelGGL(score_valu_kernel<true>, grid, dim3(256), smem, st, a);
-    else hipLaunchKernelGGL(score_valu_kernel<false>, grid, dim3(256), smem, st, a);
+    hipLaunchKernelGGL(score_valu_kernel<false>, grid, dim3(256), smem, st, a);
     return hipGetLastError();
 }
 

@@ -22,8 +22,10 @@ struct Shape {
 hipError_t launch_pool(const Shape& sh, const void* q, const void* k, void* qrep, void* krep, hipStream_t st);
 
 // Algorithm 1, score lines (four products, softmax, combine, mask, fusion).
+// stats: score_stats_bytes() of scratch (bf16: per-chunk softmax statistics; fp32: unused, 0 bytes).
+size_t score_stats_bytes(const Shape& sh);
 hipError_t launch_score(const Shape& sh, const void* qrep, const void* krep, const float* prev, float* scores,
-                        hipStream_t st);
+                        float* stats, hipStream_t st);
 
 // Algorithm 2, top-k line.
 hipError_t launch_select(const Shape& sh, const float* scores, int32_t* idx, int32_t* cnt, hipStream_t st);
