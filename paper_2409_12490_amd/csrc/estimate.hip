@@ -147,7 +147,8 @@ struct ScoreArgs {
 };
 constexpr int kScoreWaves = 8;             // waves per workgroup of the bf16 score kernels, 16 segments each
 constexpr int kScoreSegPerWg = 16 * kScoreWaves;
-constexpr int kScoreChunk = 128;           // blocks per workgroup (64 KiB of representatives in LDS)
+constexpr int kScoreChunk = 256;           // blocks per workgroup
+constexpr int kScorePiece = 64;            // blocks per LDS buffer (32 KiB of representatives), two buffers
 
 __device__ __forceinline__ float block_reduce_max(float v, float* red) {
     for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
@@ -259,11 +260,11 @@ __global__ __launch_bounds__(256) void score_valu_kernel(ScoreArgs a) {
 // score, bf16: the four representative products as bf16 MFMA GEMMs (representatives are exact bf16
 // values, so every product is exact and only the fp32 accumulation rounds).
 //
-// The blocks of a (batch, head) are cut into chunks of 128; a workgroup = 8 waves takes one chunk and 128
+// The blocks of a (batch, head) are cut into chunks of 256; a workgroup = 8 waves takes one chunk and 128
 // segments, wave w the segments 16w .. 16w+15.  Z^T = K_rep . Q_rep^T: the A operand is a tile of 32 blocks
-// of K_max (then K_min); the chunk's representatives (64 KiB) go global -> LDS once for all eight waves, all
-// loads issued up front (global_load_lds, no register staging), two workgroups per compute unit so that one
-// computes while the other loads; the B operand, column n = (segment n >> 1, representative n & 1), stays in
+// of K_max (then K_min); the chunk's representatives go global -> LDS once for all eight waves in four
+// pieces of 64 blocks (global_load_lds, no register staging, two 32 KiB buffers: the next piece lands while
+// the current one is used; two workgroups per compute unit); the B operand, column n = (segment n >> 1, representative n & 1), stays in
 // registers.  A lane then holds, for its column, 16 blocks of the tile in registers: the softmax
 // statistics over blocks are in-lane reductions plus one exchange between the wave halves, and the two
 // query representatives of a segment sit in neighbouring lanes (one DPP exchange per score).
@@ -335,34 +336,38 @@ __device__ __forceinline__ void score_setup(const ScoreArgs& a, ScoreCtx& c, uns
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) c.qf[ks] = as_bf16x8(*(const uint4*)(src + 16 * ks));
 }
-// The whole chunk, global -> LDS: instruction x of wave w (X instructions each) writes the 1 KiB at
-// 1024 * (X w + x) = rows 4 (X w + x) .. +3 (row = 2 * block + representative, 256 B); a lane's 16 bytes
-// land at lane * 16 inside that KiB, so the XOR swizzle of the 16-byte chunks by the block index (which spreads the 32 row reads of
-// a fragment over all banks) is applied to the global address.  Blocks past the last one repeat it.
-__device__ __forceinline__ void score_load_chunk(const ScoreArgs& a, const ScoreCtx& c) {
+// Piece p of the chunk, global -> LDS buffer p & 1: instruction x of wave w (X instructions each) writes the
+// 1 KiB at 1024 * (X w + x) = rows 4 (X w + x) .. +3 of the piece (row = 2 * block + representative, 256 B); a
+// lane's 16 bytes land at lane * 16 inside that KiB, so the XOR swizzle of the 16-byte chunks by the block
+// index (which spreads the 32 row reads of a fragment over all banks) is applied to the global address.
+// Blocks past the last one repeat it.
+__device__ __forceinline__ void score_load_piece(const ScoreArgs& a, const ScoreCtx& c, int p) {
     const unsigned long long pv = (unsigned long long)c.ksrc;
     const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)pv);
     const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(pv >> 32));
     const void* sbase = (const void*)(((unsigned long long)hi << 32) | lo);
-    constexpr int kPerWave = kScoreChunk / 2 / kScoreWaves;  // 1 KiB instructions per wave
+    constexpr int kPerWave = kScorePiece / 2 / kScoreWaves;  // 1 KiB instructions per wave
+    constexpr unsigned kPieceBytes = kScorePiece * 2 * kHeadDim * 2;
 #pragma unroll
     for (int x = 0; x < kPerWave; ++x) {
         const int row = 4 * (kPerWave * c.wave + x) + (c.lane >> 4);
-        const int blk = min(c.i_begin + (row >> 1), a.n2 - 1);
+        const int blk = min(c.i_begin + p * kScorePiece + (row >> 1), a.n2 - 1);
         const int lc = (c.lane & 15) ^ ((row >> 1) & 15);
         const unsigned voff = (unsigned)(((blk * 2 + (row & 1)) * kHeadDim + lc * 8) * 2);
-        const unsigned dst = __builtin_amdgcn_readfirstlane(c.lds0 + 1024u * (kPerWave * c.wave + x));
+        const unsigned dst =
+            __builtin_amdgcn_readfirstlane(c.lds0 + (p & 1) * kPieceBytes + 1024u * (kPerWave * c.wave + x));
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(voff), "s"(sbase)
                      : "memory");
     }
 }
+// every load of this wave has landed, every wave has arrived (and is done with the buffer that is filled next)
 __device__ __forceinline__ void score_chunk_ready() {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 }
 // z[b2][r] = K_rep(b2)[block 8*(r>>2) + 4*hh + (r&3) of the tile] . Q_rep[column]
-__device__ __forceinline__ void score_tile(const ScoreCtx& c, int nt, f32x16 (&z)[2]) {
-    const unsigned base = c.lds0 + nt * ScoreTile::kTileBytes + c.l32 * 512;
+__device__ __forceinline__ void score_tile(const ScoreCtx& c, int nt, f32x16 (&z)[2]) {   // tile nt of the chunk
+    const unsigned base = c.lds0 + (nt & 3) * ScoreTile::kTileBytes + c.l32 * 512;
     const int sw = c.l32 & 15;
 #pragma unroll
     for (int b2 = 0; b2 < 2; ++b2) {
@@ -382,7 +387,7 @@ __device__ __forceinline__ long long stats_index(const ScoreArgs& a, const Score
 }
 
 __global__ __launch_bounds__(64 * kScoreWaves, 4) void score_stats_kernel(ScoreArgs a) {
-    __shared__ __attribute__((aligned(1024))) unsigned char tiles[kScoreChunk * 2 * kHeadDim * 2];
+    __shared__ __attribute__((aligned(1024))) unsigned char tiles[2 * kScorePiece * 2 * kHeadDim * 2];
     ScoreCtx c;
     score_setup(a, c, (unsigned)(uintptr_t)tiles);
     if (a.domain == 1 && c.i_begin >= c.vis_wg) return;     // uniform: no visible block for any segment here
@@ -391,9 +396,12 @@ __global__ __launch_bounds__(64 * kScoreWaves, 4) void score_stats_kernel(ScoreA
     const int dom = a.domain == 0 ? a.n2 : c.vis;
     const int dom_wave = a.domain == 0 ? a.n2 : c.vis_wave; // blocks below it count for every column of the wave
     float m[2] = {-INFINITY, -INFINITY}, l[2] = {0.f, 0.f};
-    score_load_chunk(a, c);
-    score_chunk_ready();
+    score_load_piece(a, c, 0);
     for (int nt = 0; nt < c.ntile; ++nt) {
+        if ((nt & 1) == 0) {                                // a new piece: wait for it, start the next one
+            score_chunk_ready();
+            if (nt + 2 < c.ntile) score_load_piece(a, c, (nt >> 1) + 1);
+        }
         f32x16 z[2];
         score_tile(c, nt, z);
         const int i0 = c.i_begin + nt * ScoreTile::kTileBlocks + 4 * c.hh;
@@ -444,7 +452,7 @@ __global__ __launch_bounds__(64 * kScoreWaves, 4) void score_stats_kernel(ScoreA
 }
 
 __global__ __launch_bounds__(64 * kScoreWaves, 4) void score_write_kernel(ScoreArgs a) {
-    __shared__ __attribute__((aligned(1024))) unsigned char tiles[kScoreChunk * 2 * kHeadDim * 2];
+    __shared__ __attribute__((aligned(1024))) unsigned char tiles[2 * kScorePiece * 2 * kHeadDim * 2];
     ScoreCtx c;
     score_setup(a, c, (unsigned)(uintptr_t)tiles);
     const bool vec = (a.n2 & 3) == 0;                       // rows of scores are 16-byte aligned
@@ -466,7 +474,7 @@ __global__ __launch_bounds__(64 * kScoreWaves, 4) void score_write_kernel(ScoreA
     constexpr float kLog2e = 1.4426950408889634f;
     const float cs = a.scale * kLog2e;
     const int dom = a.domain == 0 ? a.n2 : c.vis;
-    score_load_chunk(a, c);                                 // the merge below runs while the chunk lands
+    score_load_piece(a, c, 0);                              // the merge below runs while the piece lands
     // merge the chunk statistics of the lane's column: the lane does the product b2 = hh, the same column's
     // lane in the other wave half does the other one (domain 1: chunks past the workgroup's last visible
     // block were never written)
@@ -498,8 +506,11 @@ __global__ __launch_bounds__(64 * kScoreWaves, 4) void score_write_kernel(ScoreA
     float fold[2];
     fold[0] = -mx[0] + __log2f(inv[0]) - 1.0f; fold[1] = -mx[1] + __log2f(inv[1]) - 1.0f;
     const bool l_pos = __builtin_amdgcn_ballot_w64(inv[0] > 0.f && inv[1] > 0.f) == ~0ull;
-    score_chunk_ready();
     for (int nt = 0; nt < c.ntile; ++nt) {
+        if ((nt & 1) == 0) {                                // a new piece: wait for it, start the next one
+            score_chunk_ready();
+            if (nt + 2 < c.ntile) score_load_piece(a, c, (nt >> 1) + 1);
+        }
         f32x16 z[2];
         const bool unseen = c.i_begin + nt * ScoreTile::kTileBlocks >= c.vis_wave_max;   // by every segment of the wave
         if (!unseen) score_tile(c, nt, z);
