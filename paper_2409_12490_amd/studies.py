@@ -1,5 +1,5 @@
 #!/usr/bin/env python3
-"""Two measurements beyond the headline benchmark, on one MI355X, printed as JSON lines.
+"""Three measurements beyond the headline benchmark, on one MI355X, printed as JSON lines.
 
 ``python -m paper_2409_12490_amd.studies fusion``
     Cost of the layer-fusion line of Algorithm 1 (S = alpha*S + (1-alpha)*S'): the estimate step at 128K with and
@@ -12,7 +12,17 @@
     block-sparse attention against the library's dense causal kernel.  The build's analogue of the paper's
     prefill-time-against-length figure (quadratic against linear growth).
 
-Inputs are the seeded synthetic Q/K/V of ``synth``; every number comes from the HIP library through the C ABI.
+``python -m paper_2409_12490_amd.studies locality``
+    The locality that the method rests on (its Eq. 3 and the overlap heat map next to it), on the generator's data at
+    16K tokens: (i) overlap |K_i ∩ K_j| / k of the exact per-query top-k token sets of queries i and j = i + delta, for
+    delta = 1 .. 4096; (ii) how much of a query's exact top-k set, and of its softmax mass, the block lists of the
+    library (estimate + select) retain, against lists of the same size made of the most recent blocks only.  A
+    quality proxy that needs no dataset and no trained weights.  The exact per-query sets are the reference here and
+    come from plain torch operations on the GPU (a dense score matrix and ``topk``); the block lists come from the
+    library.
+
+Inputs are the seeded synthetic Q/K/V of ``synth``; every latency and every block list comes from the HIP library
+through the C ABI.
 """
 from __future__ import annotations
 
@@ -88,8 +98,70 @@ def length(dev: str = "cuda:0") -> None:
         del q, k, v, out
 
 
+def locality(dev: str = "cuda:0", seq_len: int = 16384, heads=(0, 5, 10, 15, 20, 25, 30, 31), topk: int = 1024) -> None:
+    w = synth.WORKLOADS["c2_llama3_8b_16k"].replace(seq_len=seq_len, name=f"llama3_8b_{seq_len // 1024}k")
+    q, k, _ = synth.make_qkv(w, threads=min(16, os.cpu_count() or 8))
+    q, k = q.to(dev), k.to(dev)
+    n, s, G = seq_len, w.segment_size, w.n_q_heads // w.n_kv_heads
+    scale = 1.0 / (w.head_dim ** 0.5)
+    deltas = [d for d in (1, 8, 64, 512, 4096) if d < n - topk]
+    rows = torch.arange(n, device=dev)
+    for label, b, budget_blocks, local in (("paper: s=512 b=32 B=1024", 32, 1024 // 32, 0),
+                                           ("bench: s=512 b=64 B=2048 L=1", 64, 2048 // 64, 1)):
+        p = B.make_params(q, k, s, b, budget_blocks, local)
+        S, ws = B.alloc_scores(p, dev), B.alloc_workspace(p, dev)
+        idx, cnt = B.alloc_lists(p, dev)
+        B.critiprefill_estimate(p, q, k, None, S, ws)
+        B.critiprefill_select(p, S, idx, cnt)
+        torch.cuda.synchronize()
+        n1, n2, r = w.n_segments, -(-n // b), s // b
+        overlap = {d: [] for d in deltas}
+        kept_set, kept_mass, recent_set, recent_mass = [], [], [], []
+        for h in heads:
+            qh, kh = q[0, h].float(), k[0, h // G].float()
+            # exact sets: top-k visible tokens of every query with at least topk visible tokens
+            member = torch.zeros((n, n), dtype=torch.bool, device=dev)
+            prob_rows = []
+            for r0 in range(0, n, 2048):
+                z = (qh[r0:r0 + 2048] @ kh.T) * scale
+                z.masked_fill_(rows[None, :] > rows[r0:r0 + 2048, None], float("-inf"))
+                top = z.topk(topk, dim=1).indices
+                member[r0:r0 + 2048].scatter_(1, top, True)
+                prob_rows.append(torch.softmax(z, dim=1))
+            member &= rows[None, :] <= rows[:, None]          # rows with fewer than topk visible tokens: drop the padding picks
+            full = rows >= topk                               # queries whose set has exactly topk members
+            for d in deltas:
+                both = (member[:-d] & member[d:]).sum(1).float() / topk
+                overlap[d].append(float(both[full[:-d]].mean()))
+            # what the block lists keep: tokens of the listed blocks, per segment; and the same number of most recent blocks
+            tok_block = rows // b
+            listed = torch.zeros((n1, n2), dtype=torch.bool, device=dev)
+            li = idx[0, h].long(); lc = cnt[0, h].long()
+            valid = torch.arange(li.shape[1], device=dev)[None, :] < lc[:, None]
+            listed.scatter_(1, li.clamp(min=0), valid)
+            seg = rows // s
+            recent = torch.zeros((n1, n2), dtype=torch.bool, device=dev)
+            blocks = torch.arange(n2, device=dev)
+            last = (torch.arange(n1, device=dev) + 1) * r           # first block after the segment
+            recent |= (blocks[None, :] < last[:, None]) & (blocks[None, :] >= (last - lc)[:, None])
+            prob = torch.cat(prob_rows)
+            for mask_blocks, out_set, out_mass in ((listed, kept_set, kept_mass), (recent, recent_set, recent_mass)):
+                tok_mask = mask_blocks[seg][:, tok_block]           # [query, token]: the token's block is in the query's list
+                out_set.append(float(((member & tok_mask).sum(1).float() / topk)[full].mean()))
+                out_mass.append(float((prob * tok_mask).sum(1)[full].mean()))
+            del member, prob, prob_rows
+        mean = lambda xs: round(sum(xs) / len(xs), 4)
+        print(json.dumps({"study": "locality", "seq_len": n, "setting": label, "heads": list(heads), "topk_tokens": topk,
+                          "overlap_of_exact_topk_sets_by_query_distance": {str(d): mean(v) for d, v in overlap.items()},
+                          "kept_by_block_lists": {"of_exact_topk_set": mean(kept_set), "of_softmax_mass": mean(kept_mass)},
+                          "kept_by_most_recent_blocks_same_count": {"of_exact_topk_set": mean(recent_set),
+                                                                     "of_softmax_mass": mean(recent_mass)},
+                          "mean_listed_blocks": round(float(cnt[0, list(heads)].float().mean()), 2),
+                          "blocks_total": n2}), flush=True)
+
+
 def main(argv) -> int:
-    if len(argv) != 2 or argv[1] not in ("fusion", "length"):
+    if len(argv) != 2 or argv[1] not in ("fusion", "length", "locality"):
         print(__doc__)
         return 2
     if not torch.cuda.is_available():
@@ -97,7 +169,7 @@ def main(argv) -> int:
         return 2
     B.load()
     torch.cuda.set_device(0)
-    {"fusion": fusion, "length": length}[argv[1]]()
+    {"fusion": fusion, "length": length, "locality": locality}[argv[1]]()
     return 0
 
 
