@@ -6,6 +6,7 @@
  *   critiprefill_estimate          Algorithm 1 "Estimation of Query Criticality in One Layer"
  *   critiprefill_select            Algorithm 2 "Pruned Attention", the argtop_k(S[j], B/block size) step
  *   critiprefill_sparse_attn       Algorithm 2, the per-segment attention loop
+ *   critiprefill_select_shared / critiprefill_sparse_attn_shared   the same two steps with one list per KV head
  *   critiprefill_dense_causal_attn Eq. 2 (O = softmax(Q K^T / sqrt(d)) V) with the prefill causal mask
  *
  * Conventions common to all entry points
@@ -102,6 +103,21 @@ int critiprefill_select(const critiprefill_params *p, const float *scores,
 int critiprefill_sparse_attn(const critiprefill_params *p, const void *q, const void *k, const void *v,
                              const int32_t *block_idx, const int32_t *block_cnt,
                              void *out, float *lse, void *hip_stream);
+
+/*
+ * Extension of the paper's single-head description (it gives no rule for sharing a list between heads):
+ * ONE list per (batch, KV head, segment) for all query heads of that KV head, taken from the element-wise
+ * maximum of their scores.  critiprefill_select_shared reads scores[batch, n_q_heads, n1, n2] and writes
+ * block_idx[batch, n_kv_heads, n1, list_len] / block_cnt[batch, n_kv_heads, n1] by the same rule as
+ * critiprefill_select applied to max over the group's heads; critiprefill_sparse_attn_shared is
+ * critiprefill_sparse_attn reading those lists (query head h uses the list of KV head
+ * h / (n_q_heads / n_kv_heads)).  Same argument checks and errors as the per-head entry points.
+ */
+int critiprefill_select_shared(const critiprefill_params *p, const float *scores,
+                               int32_t *block_idx, int32_t *block_cnt, void *hip_stream);
+int critiprefill_sparse_attn_shared(const critiprefill_params *p, const void *q, const void *k, const void *v,
+                                    const int32_t *block_idx, const int32_t *block_cnt,
+                                    void *out, float *lse, void *hip_stream);
 
 /* Eq. 2 with the causal mask u <= t: the dense baseline.  Same tensors as sparse_attn, no lists. */
 int critiprefill_dense_causal_attn(const critiprefill_params *p, const void *q, const void *k, const void *v,

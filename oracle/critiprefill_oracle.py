@@ -19,6 +19,8 @@ What it follows:
   step, plus the always-kept local and diagonal blocks.
 * ``sparse_attention`` – Algorithm 2, the per-segment loop: gather the listed
   blocks, softmax(Q_j K^T / sqrt(d)), times V.
+* ``shared_group_scores`` / ``expand_shared_lists`` – an extension, not in the
+  paper: one list per KV head from the maximum of its query heads' scores.
 
 Readings taken where the paper is silent (each is a parameter or stated here):
 
@@ -226,6 +228,29 @@ def select(scores, segment_size, block_size, budget_blocks, local_blocks=0):
                 idx[b, h, j, :len(lst)] = lst
                 cnt[b, h, j] = len(lst)
     return idx, cnt
+
+
+def shared_group_scores(scores, n_kv_heads):
+    """Extension beyond the paper (which describes one head and gives no rule for sharing a list between
+    heads): the score a KV head's shared list is chosen from is the element-wise maximum of S over the
+    query heads that read that KV head.  scores [B,Hq,n1,n2] -> [B,Hkv,n1,n2].  ``select`` on the result
+    gives one list per (batch, KV head, segment); ``expand_shared_lists`` hands it to every query head."""
+    scores = np.asarray(scores)
+    B, Hq, n1, n2 = scores.shape
+    G = Hq // n_kv_heads
+    out = np.empty((B, n_kv_heads, n1, n2), dtype=scores.dtype)
+    for g in range(n_kv_heads):
+        members = [h for h in range(Hq) if _kv_head(h, Hq, n_kv_heads) == g]
+        assert len(members) == G
+        out[:, g] = scores[:, members].max(axis=1)
+    return out
+
+
+def expand_shared_lists(block_idx, block_cnt, n_q_heads):
+    """Per-KV-head lists [B,Hkv,n1,L] / [B,Hkv,n1] repeated for every query head of the group."""
+    Hkv = block_idx.shape[1]
+    heads = [_kv_head(h, n_q_heads, Hkv) for h in range(n_q_heads)]
+    return block_idx[:, heads].copy(), block_cnt[:, heads].copy()
 
 
 def sparse_attention(q, k, v, block_idx, block_cnt, segment_size, block_size,

@@ -16,7 +16,8 @@ _lib = None
 
 CP_DTYPE_FP32, CP_DTYPE_BF16 = 0, 1
 EXPORTS = ["critiprefill_list_len", "critiprefill_workspace_bytes", "critiprefill_estimate",
-           "critiprefill_select", "critiprefill_sparse_attn", "critiprefill_dense_causal_attn",
+           "critiprefill_select", "critiprefill_sparse_attn", "critiprefill_select_shared",
+           "critiprefill_sparse_attn_shared", "critiprefill_dense_causal_attn",
            "critiprefill_strerror", "critiprefill_version"]
 
 
@@ -54,6 +55,8 @@ def load():
     lib.critiprefill_estimate.argtypes = [P, vp, vp, vp, vp, vp, sz, vp]; lib.critiprefill_estimate.restype = ctypes.c_int
     lib.critiprefill_select.argtypes = [P, vp, vp, vp, vp]; lib.critiprefill_select.restype = ctypes.c_int
     lib.critiprefill_sparse_attn.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp]; lib.critiprefill_sparse_attn.restype = ctypes.c_int
+    lib.critiprefill_select_shared.argtypes = [P, vp, vp, vp, vp]; lib.critiprefill_select_shared.restype = ctypes.c_int
+    lib.critiprefill_sparse_attn_shared.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp]; lib.critiprefill_sparse_attn_shared.restype = ctypes.c_int
     lib.critiprefill_dense_causal_attn.argtypes = [P, vp, vp, vp, vp, vp, vp]; lib.critiprefill_dense_causal_attn.restype = ctypes.c_int
     lib.critiprefill_strerror.argtypes = [ctypes.c_int]; lib.critiprefill_strerror.restype = ctypes.c_char_p
     lib.critiprefill_version.argtypes = []; lib.critiprefill_version.restype = ctypes.c_int
@@ -133,6 +136,17 @@ def critiprefill_sparse_attn(p, q, k, v, block_idx, block_cnt, out, lse=None, st
            "critiprefill_sparse_attn")
 
 
+def critiprefill_select_shared(p, scores, block_idx, block_cnt, stream=None):
+    _check(load().critiprefill_select_shared(ctypes.byref(p), _ptr(scores), _ptr(block_idx), _ptr(block_cnt),
+                                             _stream(stream)), "critiprefill_select_shared")
+
+
+def critiprefill_sparse_attn_shared(p, q, k, v, block_idx, block_cnt, out, lse=None, stream=None):
+    _check(load().critiprefill_sparse_attn_shared(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(block_idx),
+                                                  _ptr(block_cnt), _ptr(out), _ptr(lse), _stream(stream)),
+           "critiprefill_sparse_attn_shared")
+
+
 def critiprefill_dense_causal_attn(p, q, k, v, out, lse=None, stream=None):
     _check(load().critiprefill_dense_causal_attn(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse),
                                                  _stream(stream)), "critiprefill_dense_causal_attn")
@@ -155,6 +169,14 @@ def alloc_lists(p: Params, device="cuda"):
     ll = critiprefill_list_len(p)
     idx = torch.empty((p.batch, p.n_q_heads, n_segments(p), ll), dtype=torch.int32, device=device)
     cnt = torch.empty((p.batch, p.n_q_heads, n_segments(p)), dtype=torch.int32, device=device)
+    return idx, cnt
+
+
+def alloc_shared_lists(p: Params, device="cuda"):
+    """Lists of critiprefill_select_shared: one per (batch, KV head, segment)."""
+    ll = critiprefill_list_len(p)
+    idx = torch.empty((p.batch, p.n_kv_heads, n_segments(p), ll), dtype=torch.int32, device=device)
+    cnt = torch.empty((p.batch, p.n_kv_heads, n_segments(p)), dtype=torch.int32, device=device)
     return idx, cnt
 
 

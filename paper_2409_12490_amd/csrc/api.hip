@@ -115,22 +115,22 @@ int critiprefill_estimate(const critiprefill_params* p, const void* q, const voi
     return CP_OK;
 }
 
-int critiprefill_select(const critiprefill_params* p, const float* scores, int32_t* block_idx, int32_t* block_cnt,
-                        void* hip_stream) {
+namespace {
+int select_common(const critiprefill_params* p, const float* scores, int32_t* block_idx, int32_t* block_cnt,
+                  bool shared, void* hip_stream) {
     cp::Shape sh;
     const int e = make_shape(p, &sh);
     if (e != CP_OK) return e;
     if (!scores || !block_idx || !block_cnt) return CP_ERR_NULL;
     if (sh.n2 > kMaxBlocks) return CP_ERR_UNSUPPORTED;
     if (!aligned16(scores) || !aligned16(block_idx) || !aligned16(block_cnt)) return CP_ERR_ALIGN;
-    if (cp::launch_select(sh, scores, block_idx, block_cnt, (hipStream_t)hip_stream) != hipSuccess)
+    if (cp::launch_select(sh, scores, block_idx, block_cnt, shared, (hipStream_t)hip_stream) != hipSuccess)
         return CP_ERR_LAUNCH;
     return CP_OK;
 }
 
-int critiprefill_sparse_attn(const critiprefill_params* p, const void* q, const void* k, const void* v,
-                             const int32_t* block_idx, const int32_t* block_cnt, void* out, float* lse,
-                             void* hip_stream) {
+int sparse_common(const critiprefill_params* p, const void* q, const void* k, const void* v, const int32_t* block_idx,
+                  const int32_t* block_cnt, bool shared, void* out, float* lse, void* hip_stream) {
     cp::Shape sh;
     int e = make_shape(p, &sh);
     if (e != CP_OK) return e;
@@ -140,9 +140,32 @@ int critiprefill_sparse_attn(const critiprefill_params* p, const void* q, const 
     if (sh.dtype == CP_DTYPE_BF16 && sh.list_len > cp::kMaxListBf16) return CP_ERR_UNSUPPORTED;
     hipStream_t st = (hipStream_t)hip_stream;
     const hipError_t he = sh.dtype == CP_DTYPE_BF16
-                              ? cp::launch_attn_bf16(sh, q, k, v, block_idx, block_cnt, out, lse, st)
-                              : cp::launch_attn_fp32(sh, q, k, v, block_idx, block_cnt, out, lse, st);
+                              ? cp::launch_attn_bf16(sh, q, k, v, block_idx, block_cnt, shared, out, lse, st)
+                              : cp::launch_attn_fp32(sh, q, k, v, block_idx, block_cnt, shared, out, lse, st);
     return he == hipSuccess ? CP_OK : CP_ERR_LAUNCH;
+}
+}  // namespace
+
+int critiprefill_select(const critiprefill_params* p, const float* scores, int32_t* block_idx, int32_t* block_cnt,
+                        void* hip_stream) {
+    return select_common(p, scores, block_idx, block_cnt, false, hip_stream);
+}
+
+int critiprefill_select_shared(const critiprefill_params* p, const float* scores, int32_t* block_idx,
+                               int32_t* block_cnt, void* hip_stream) {
+    return select_common(p, scores, block_idx, block_cnt, true, hip_stream);
+}
+
+int critiprefill_sparse_attn(const critiprefill_params* p, const void* q, const void* k, const void* v,
+                             const int32_t* block_idx, const int32_t* block_cnt, void* out, float* lse,
+                             void* hip_stream) {
+    return sparse_common(p, q, k, v, block_idx, block_cnt, false, out, lse, hip_stream);
+}
+
+int critiprefill_sparse_attn_shared(const critiprefill_params* p, const void* q, const void* k, const void* v,
+                                    const int32_t* block_idx, const int32_t* block_cnt, void* out, float* lse,
+                                    void* hip_stream) {
+    return sparse_common(p, q, k, v, block_idx, block_cnt, true, out, lse, hip_stream);
 }
 
 int critiprefill_dense_causal_attn(const critiprefill_params* p, const void* q, const void* k, const void* v,
@@ -153,8 +176,8 @@ int critiprefill_dense_causal_attn(const critiprefill_params* p, const void* q, 
     if ((e = check_attn(sh, q, k, v, out, lse)) != CP_OK) return e;
     hipStream_t st = (hipStream_t)hip_stream;
     const hipError_t he = sh.dtype == CP_DTYPE_BF16
-                              ? cp::launch_attn_bf16(sh, q, k, v, nullptr, nullptr, out, lse, st)
-                              : cp::launch_attn_fp32(sh, q, k, v, nullptr, nullptr, out, lse, st);
+                              ? cp::launch_attn_bf16(sh, q, k, v, nullptr, nullptr, false, out, lse, st)
+                              : cp::launch_attn_fp32(sh, q, k, v, nullptr, nullptr, false, out, lse, st);
     return he == hipSuccess ? CP_OK : CP_ERR_LAUNCH;
 }
 

@@ -58,6 +58,7 @@ struct ArgsB {
     const uint16_t* q; const uint16_t* k; const uint16_t* v; const int32_t* idx; const int32_t* cnt;
     uint16_t* out; float* lse;
     int batch, hq, hkv, n, s, b, n1, list_len, qtiles;
+    int shared_lists;                     // lists are per (batch, KV head, segment) instead of per query head
     float scale_log2e, scale;
     long long qs0, qs1, qs2, ks0, ks1, ks2, os0, os1, os2;
 };
@@ -160,7 +161,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
     // ---- the virtual token list --------------------------------------------------------------
     int count = 0;
     if (!DENSE) {
-        const long long lrow = ((long long)bb * a.hq + h) * a.n1 + j;
+        const long long lrow = a.shared_lists ? ((long long)bb * a.hkv + g) * a.n1 + j : ((long long)bb * a.hq + h) * a.n1 + j;
         const int32_t* list = a.idx + lrow * a.list_len;
         count = a.cnt[lrow];
         for (int x = tid; x < count; x += 512) *LDS_PTR(int, lds0 + kListOff + x * 4) = list[x];
@@ -591,12 +592,12 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
 }  // namespace
 
 hipError_t launch_attn_bf16(const Shape& sh, const void* q, const void* k, const void* v, const int32_t* idx,
-                            const int32_t* cnt, void* out, float* lse, hipStream_t st) {
+                            const int32_t* cnt, bool shared_lists, void* out, float* lse, hipStream_t st) {
     ArgsB a;
     a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.idx = idx; a.cnt = cnt;
     a.out = (uint16_t*)out; a.lse = lse;
     a.batch = sh.batch; a.hq = sh.hq; a.hkv = sh.hkv; a.n = sh.n; a.s = sh.s; a.b = sh.b; a.n1 = sh.n1;
-    a.list_len = sh.list_len;
+    a.list_len = sh.list_len; a.shared_lists = shared_lists ? 1 : 0;
     a.scale = sh.attn_scale;
     a.scale_log2e = sh.attn_scale * 1.4426950408889634f;
     a.qs0 = sh.qs[0]; a.qs1 = sh.qs[1]; a.qs2 = sh.qs[2];

@@ -12,6 +12,7 @@ struct Args32 {
     const float* q; const float* k; const float* v; const int32_t* idx; const int32_t* cnt;
     float* out; float* lse;
     int hq, hkv, n, s, b, n1, list_len, qtiles;   // qtiles: per segment (sparse) or per sequence (dense)
+    int shared_lists;                             // lists are per (batch, KV head, segment) instead of per query head
     float scale;
     long long qs0, qs1, qs2, ks0, ks1, ks2, os0, os1, os2;
 };
@@ -49,7 +50,7 @@ __global__ __launch_bounds__(256) void attn_fp32_kernel(Args32 a) {
 
     const int32_t* list = nullptr; int count = 0;
     if (!DENSE) {
-        const long long lrow = ((long long)bb * a.hq + h) * a.n1 + j;
+        const long long lrow = a.shared_lists ? ((long long)bb * a.hkv + g) * a.n1 + j : ((long long)bb * a.hq + h) * a.n1 + j;
         list = a.idx + lrow * a.list_len;
         count = a.cnt[lrow];
     }
@@ -150,11 +151,12 @@ __global__ __launch_bounds__(256) void attn_fp32_kernel(Args32 a) {
 }  // namespace
 
 hipError_t launch_attn_fp32(const Shape& sh, const void* q, const void* k, const void* v, const int32_t* idx,
-                            const int32_t* cnt, void* out, float* lse, hipStream_t st) {
+                            const int32_t* cnt, bool shared_lists, void* out, float* lse, hipStream_t st) {
     Args32 a;
     a.q = (const float*)q; a.k = (const float*)k; a.v = (const float*)v; a.idx = idx; a.cnt = cnt;
     a.out = (float*)out; a.lse = lse;
     a.hq = sh.hq; a.hkv = sh.hkv; a.n = sh.n; a.s = sh.s; a.b = sh.b; a.n1 = sh.n1; a.list_len = sh.list_len;
+    a.shared_lists = shared_lists ? 1 : 0;
     a.scale = sh.attn_scale;
     a.qs0 = sh.qs[0]; a.qs1 = sh.qs[1]; a.qs2 = sh.qs[2];
     a.ks0 = sh.kvs[0]; a.ks1 = sh.kvs[1]; a.ks2 = sh.kvs[2];

@@ -27,13 +27,15 @@ size_t score_stats_bytes(const Shape& sh);
 hipError_t launch_score(const Shape& sh, const void* qrep, const void* krep, const float* prev, float* scores,
                         float* stats, hipStream_t st);
 
-// Algorithm 2, top-k line.
-hipError_t launch_select(const Shape& sh, const float* scores, int32_t* idx, int32_t* cnt, hipStream_t st);
+// Algorithm 2, top-k line.  shared: one list per (batch, KV head, segment) from the max of the scores of the
+// KV head's query heads (idx [B,Hkv,n1,list_len], cnt [B,Hkv,n1]) instead of one per query head.
+hipError_t launch_select(const Shape& sh, const float* scores, int32_t* idx, int32_t* cnt, bool shared, hipStream_t st);
 
 // Algorithm 2 attention loop (idx != nullptr) or Eq. 2 dense causal attention (idx == nullptr).
+// shared_lists: idx/cnt hold one list per KV head (see launch_select) instead of one per query head.
 hipError_t launch_attn_bf16(const Shape& sh, const void* q, const void* k, const void* v, const int32_t* idx,
-                            const int32_t* cnt, void* out, float* lse, hipStream_t st);
+                            const int32_t* cnt, bool shared_lists, void* out, float* lse, hipStream_t st);
 hipError_t launch_attn_fp32(const Shape& sh, const void* q, const void* k, const void* v, const int32_t* idx,
-                            const int32_t* cnt, void* out, float* lse, hipStream_t st);
+                            const int32_t* cnt, bool shared_lists, void* out, float* lse, hipStream_t st);
 
 }  // namespace cp

@@ -13,9 +13,11 @@ namespace {
 
 struct SelectArgs {
     const float* scores; int32_t* idx; int32_t* cnt;
-    long long rows;            // B*H*n1
+    long long rows;            // B*H*n1 lists (H = query heads, or KV heads when the lists are shared)
     int n1, n2, r, budget, local, list_len;
+    int group;                 // shared lists: query heads per KV head, whose scores are merged by max
 };
+
 
 __device__ __forceinline__ uint32_t ordered_key(float x) {
     uint32_t u = __float_as_uint(x);
@@ -23,12 +25,24 @@ __device__ __forceinline__ uint32_t ordered_key(float x) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// key of block i for list row `row`: the row's own score, or (SHARED) the largest score of the block among the
+// query heads of the row's KV head (scores [B, Hq, n1, n2], query head = KV head * group + member)
+template <bool SHARED>
+__device__ __forceinline__ uint32_t row_key(const SelectArgs& a, long long row, int j, int i) {
+    if (!SHARED) return ordered_key(a.scores[row * a.n2 + i]);
+    const long long bh = row / a.n1;
+    uint32_t kx = 0;
+    for (int g2 = 0; g2 < a.group; ++g2)
+        kx = max(kx, ordered_key(a.scores[((bh * a.group + g2) * a.n1 + j) * a.n2 + i]));
+    return kx;
+}
+
 __device__ __forceinline__ int wave_sum(int v) {
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
     return v;
 }
 
-template <int PER_LANE>
+template <int PER_LANE, bool SHARED>
 __global__ __launch_bounds__(256) void select_kernel(SelectArgs a) {
     const int lane = threadIdx.x & 63;
     const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -39,14 +53,13 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a) {
     const int n_local = min(a.local, diag_lo);
     const int n_cand = diag_lo - n_local;
     const int kj = min(a.budget, n_cand);
-    const float* s = a.scores + row * a.n2;
     int32_t* out = a.idx + row * a.list_len;
 
     uint32_t key[PER_LANE];
 #pragma unroll
     for (int m = 0; m < PER_LANE; ++m) {
         const int i = m * 64 + lane;
-        const uint32_t kx = ordered_key(s[min(i, a.n2 - 1)]);   // unconditional load: no per-element exec masks to keep
+        const uint32_t kx = row_key<SHARED>(a, row, j, min(i, a.n2 - 1));   // unconditional load: no per-element exec masks to keep
         key[m] = (i < n_cand) ? kx : 0u;                   // 0 is below every trial threshold: never counted
     }
     int written = 0;
@@ -91,6 +104,7 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a) {
 // Rows longer than 4096 blocks: one 256-thread workgroup per row, thread t owns blocks t, t+256, ...; the same
 // radix search with the wave counts added up through LDS, and a compaction whose prefix runs over the four waves.
 constexpr int kWideThreads = 256, kWidePerThread = 32;       // 8192 blocks
+template <bool SHARED>
 __global__ __launch_bounds__(kWideThreads) void select_wide_kernel(SelectArgs a) {
     __shared__ int part[2][4];                             // double-buffered per-wave partial counts
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -101,14 +115,13 @@ __global__ __launch_bounds__(kWideThreads) void select_wide_kernel(SelectArgs a)
     const int n_local = min(a.local, diag_lo);
     const int n_cand = diag_lo - n_local;
     const int kj = min(a.budget, n_cand);
-    const float* s = a.scores + row * a.n2;
     int32_t* out = a.idx + row * a.list_len;
 
     uint32_t key[kWidePerThread];
 #pragma unroll
     for (int m = 0; m < kWidePerThread; ++m) {
         const int i = m * kWideThreads + tid;
-        const uint32_t kx = ordered_key(s[min(i, a.n2 - 1)]);
+        const uint32_t kx = row_key<SHARED>(a, row, j, min(i, a.n2 - 1));
         key[m] = (i < n_cand) ? kx : 0u;                   // 0 is below every trial threshold: never counted
     }
     int step = 0;
@@ -171,20 +184,26 @@ __global__ __launch_bounds__(kWideThreads) void select_wide_kernel(SelectArgs a)
 
 }  // namespace
 
-hipError_t launch_select(const Shape& sh, const float* scores, int32_t* idx, int32_t* cnt, hipStream_t st) {
+template <bool SHARED>
+hipError_t launch_select_impl(const Shape& sh, const float* scores, int32_t* idx, int32_t* cnt, hipStream_t st) {
     SelectArgs a;
     a.scores = scores; a.idx = idx; a.cnt = cnt;
-    a.rows = (long long)sh.batch * sh.hq * sh.n1;
+    a.rows = (long long)sh.batch * (SHARED ? sh.hkv : sh.hq) * sh.n1;
+    a.group = sh.hq / sh.hkv;
     a.n1 = sh.n1; a.n2 = sh.n2; a.r = sh.r; a.budget = sh.budget; a.local = sh.local; a.list_len = sh.list_len;
     const unsigned grid = (unsigned)((a.rows + 3) / 4);
-    if (sh.n2 <= 64 * 8) hipLaunchKernelGGL(select_kernel<8>, dim3(grid), dim3(256), 0, st, a);
-    else if (sh.n2 <= 64 * 32) hipLaunchKernelGGL(select_kernel<32>, dim3(grid), dim3(256), 0, st, a);
-    else if (sh.n2 <= 64 * 64) hipLaunchKernelGGL(select_kernel<64>, dim3(grid), dim3(256), 0, st, a);
+    if (sh.n2 <= 64 * 8) hipLaunchKernelGGL((select_kernel<8, SHARED>), dim3(grid), dim3(256), 0, st, a);
+    else if (sh.n2 <= 64 * 32) hipLaunchKernelGGL((select_kernel<32, SHARED>), dim3(grid), dim3(256), 0, st, a);
+    else if (sh.n2 <= 64 * 64) hipLaunchKernelGGL((select_kernel<64, SHARED>), dim3(grid), dim3(256), 0, st, a);
     else {
         if (a.rows > 0x7fffffffLL || sh.n2 > kWideThreads * kWidePerThread) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(select_wide_kernel, dim3((unsigned)a.rows), dim3(kWideThreads), 0, st, a);
+        hipLaunchKernelGGL(select_wide_kernel<SHARED>, dim3((unsigned)a.rows), dim3(kWideThreads), 0, st, a);
     }
     return hipGetLastError();
+}
+
+hipError_t launch_select(const Shape& sh, const float* scores, int32_t* idx, int32_t* cnt, bool shared, hipStream_t st) {
+    return shared ? launch_select_impl<true>(sh, scores, idx, cnt, st) : launch_select_impl<false>(sh, scores, idx, cnt, st);
 }
 
 }  // namespace cp

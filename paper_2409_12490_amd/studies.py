@@ -1,5 +1,5 @@
 #!/usr/bin/env python3
-"""Three measurements beyond the headline benchmark, on one MI355X, printed as JSON lines.
+"""Four measurements beyond the headline benchmark, on one MI355X, printed as JSON lines.
 
 ``python -m paper_2409_12490_amd.studies fusion``
     Cost of the layer-fusion line of Algorithm 1 (S = alpha*S + (1-alpha)*S'): the estimate step at 128K with and
@@ -20,6 +20,12 @@
     quality proxy that needs no dataset and no trained weights.  The exact per-query sets are the reference here and
     come from plain torch operations on the GPU (a dense score matrix and ``topk``); the block lists come from the
     library.
+
+``python -m paper_2409_12490_amd.studies shared``
+    One block list per KV head (from the maximum of its query heads' scores) instead of one per query head, an
+    extension the paper does not describe: latency of select + sparse attention and the change of the output error
+    (against the library's dense kernel) at 128K, for the budget of the benchmark and for a budget G times larger
+    (the union of G per-head lists is at most that long).
 
 Inputs are the seeded synthetic Q/K/V of ``synth``; every latency and every block list comes from the HIP library
 through the C ABI.
@@ -160,8 +166,42 @@ def locality(dev: str = "cuda:0", seq_len: int = 16384, heads=(0, 5, 10, 15, 20,
                           "blocks_total": n2}), flush=True)
 
 
+def shared(dev: str = "cuda:0") -> None:
+    w = synth.WORKLOADS["c3_llama3_8b_128k"]
+    q, k, v = synth.make_qkv(w, threads=min(16, os.cpu_count() or 8))
+    q, k, v = q.to(dev), k.to(dev), v.to(dev)
+    out, dense = torch.empty_like(q), torch.empty_like(q)
+    p0 = B.make_params(q, k, w.segment_size, w.block_size, w.budget_blocks, w.local_blocks, out=out)
+    B.critiprefill_dense_causal_attn(p0, q, k, v, dense, None)
+    S, ws = B.alloc_scores(p0, dev), B.alloc_workspace(p0, dev)
+    B.critiprefill_estimate(p0, q, k, None, S, ws)
+    G = w.n_q_heads // w.n_kv_heads
+
+    def err(o):
+        d = (o.float() - dense.float())
+        return float(d.abs().max()), float(d.norm() / dense.float().norm())
+
+    for budget in (w.budget_blocks, G * w.budget_blocks):
+        p = B.make_params(q, k, w.segment_size, w.block_size, budget, w.local_blocks, out=out)
+        for kind in ("per query head", "per KV head"):
+            if kind == "per query head":
+                idx, cnt = B.alloc_lists(p, dev)
+                sel = lambda: B.critiprefill_select(p, S, idx, cnt)
+                att = lambda: B.critiprefill_sparse_attn(p, q, k, v, idx, cnt, out, None)
+            else:
+                idx, cnt = B.alloc_shared_lists(p, dev)
+                sel = lambda: B.critiprefill_select_shared(p, S, idx, cnt)
+                att = lambda: B.critiprefill_sparse_attn_shared(p, q, k, v, idx, cnt, out, None)
+            sel(); att(); torch.cuda.synchronize()
+            e_max, e_rel = err(out)
+            print(json.dumps({"study": "shared", "workload": w.name, "lists": kind, "budget_blocks": budget,
+                              "select_ms": round(_time(sel, 10), 4), "sparse_attn_ms": round(_time(att, 10), 4),
+                              "max_abs_vs_dense": round(e_max, 4), "rel_l2_vs_dense": round(e_rel, 5),
+                              "mean_listed_blocks": round(float(cnt.float().mean()), 2)}), flush=True)
+
+
 def main(argv) -> int:
-    if len(argv) != 2 or argv[1] not in ("fusion", "length", "locality"):
+    if len(argv) != 2 or argv[1] not in ("fusion", "length", "locality", "shared"):
         print(__doc__)
         return 2
     if not torch.cuda.is_available():
@@ -169,7 +209,7 @@ def main(argv) -> int:
         return 2
     B.load()
     torch.cuda.set_device(0)
-    {"fusion": fusion, "length": length, "locality": locality}[argv[1]]()
+    {"fusion": fusion, "length": length, "locality": locality, "shared": shared}[argv[1]]()
     return 0
 
 

@@ -45,6 +45,24 @@ def gpu_sparse(w, q, k, v, idx, cnt, want_lse=True, **kw):
     return out, lse
 
 
+def gpu_select_shared(w, q, k, S):
+    p = params_for(w, q, k)
+    idx, cnt = B.alloc_shared_lists(p)
+    idx.fill_(-7)
+    B.critiprefill_select_shared(p, S, idx, cnt)
+    torch.cuda.synchronize()
+    return idx, cnt
+
+
+def gpu_sparse_shared(w, q, k, v, idx, cnt, **kw):
+    out = torch.full_like(q, float("nan"))
+    p = params_for(w, q, k, out=out, **kw)
+    lse = torch.full(q.shape[:3], float("nan"), dtype=torch.float32, device=q.device)
+    B.critiprefill_sparse_attn_shared(p, q, k, v, idx, cnt, out, lse)
+    torch.cuda.synchronize()
+    return out, lse
+
+
 def gpu_dense(w, q, k, v, want_lse=True, **kw):
     out = torch.full_like(q, float("nan"))
     p = params_for(w, q, k, out=out, **kw)

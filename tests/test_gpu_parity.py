@@ -129,6 +129,28 @@ def test_sparse_attention_with_checker_lists(case):
 
 
 @pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
+def test_shared_lists_per_kv_head(case):
+    """One list per KV head from the maximum of the group's scores: selection bit-exact on the same fp32
+    scores, attention with those lists against the checker run with the list handed to every head."""
+    w, q, k, v = make(case)
+    print("case", case, flush=True)
+    _, Sd, _, _ = oracle_lists(w, q, k)
+    Sg = O.shared_group_scores(Sd, w.n_kv_heads)
+    idx_o, cnt_o = O.select(Sg, w.segment_size, w.block_size, w.budget_blocks, w.local_blocks)
+    idx_g, cnt_g = H.gpu_select_shared(w, q.to(DEV), k.to(DEV), torch.from_numpy(Sd).to(DEV))
+    assert tuple(idx_g.shape) == idx_o.shape
+    H.check_selection(Sg, idx_o, cnt_o, idx_g, cnt_g, w, exact=True)
+    idx_h, cnt_h = O.expand_shared_lists(idx_o, cnt_o, w.n_q_heads)
+    o_ref, lse_ref = O.sparse_attention(synth.to_f64(q), synth.to_f64(k), synth.to_f64(v), idx_h, cnt_h,
+                                        w.segment_size, w.block_size)
+    out, lse = H.gpu_sparse_shared(w, q.to(DEV), k.to(DEV), v.to(DEV), idx_g, cnt_g)
+    err = H.max_abs(out.float().cpu().numpy(), o_ref)
+    print("max abs err", err, flush=True)
+    assert err <= H.TOL_OUT[w.dtype]
+    assert H.max_abs(lse.cpu().numpy(), lse_ref) <= (2e-2 if w.dtype == "bf16" else 1e-4)
+
+
+@pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
 def test_dense_causal_attention(case):
     w, q, k, v = make(case)
     print("case", case, flush=True)

@@ -382,3 +382,32 @@ def test_attended_pairs_counts_causal_triangle():
     for j in range(n1):
         idx[0, 0, j, :r] = np.arange(j * r, (j + 1) * r); cnt[0, 0, j] = r
     assert O.attended_pairs(idx, cnt, n, s, b)[0, 0] == n1 * s * (s + 1) // 2
+
+
+def test_shared_group_scores_bruteforce_and_special_cases():
+    """The shared-list extension: element by element against python loops; one head per group is the
+    identity; a list chosen from the group maximum contains each member head's single best candidate."""
+    rng = np.random.default_rng(5)
+    B_, Hq, Hkv, n1, n2, r = 2, 6, 2, 5, 20, 4
+    S = rng.random((B_, Hq, n1, n2)).astype(np.float32)
+    Sg = O.shared_group_scores(S, Hkv)
+    G = Hq // Hkv
+    for b in range(B_):
+        for g in range(Hkv):
+            for j in range(n1):
+                for i in range(n2):
+                    assert Sg[b, g, j, i] == max(S[b, g * G + m, j, i] for m in range(G))
+    np.testing.assert_array_equal(O.shared_group_scores(S, Hq), S)
+    idx_g, cnt_g = O.select(Sg, r * 2, 2, 3, 0)
+    idx_h, cnt_h = O.expand_shared_lists(idx_g, cnt_g, Hq)
+    assert idx_h.shape[1] == Hq
+    for b in range(B_):
+        for h in range(Hq):
+            np.testing.assert_array_equal(idx_h[b, h], idx_g[b, h // G])
+            for j in range(1, n1):
+                n_cand = j * r
+                best = int(np.argmax(S[b, h, j, :n_cand]))
+                shared = idx_g[b, h // G, j, :cnt_g[b, h // G, j]]
+                # the head's best block is in the shared list unless 3 blocks of the group beat it
+                beaten_by = int((Sg[b, h // G, j, :n_cand] > S[b, h, j, best]).sum())
+                assert best in shared or beaten_by >= 3
