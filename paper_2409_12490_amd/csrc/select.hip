@@ -3,7 +3,8 @@
 //
 // One wavefront per (batch, head, segment) row.  The row lives in registers (lane l owns blocks
 // l, l+64, ...).  Scores are mapped to order-preserving unsigned keys; the k-th largest key is found
-// by an MSB-first radix search (one wave-wide count per bit); everything above it is taken, ties at
+// by an MSB-first radix search (one wave-wide count per bit: a compare per key, the lane masks counted on the
+// scalar unit); everything above it is taken, ties at
 // the threshold go to the smallest indices, and the result is compacted in index order, so the
 // list comes out ascending.
 #include "kernels.h"
@@ -67,15 +68,15 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a) {
         uint32_t thr = 0;
         for (int bit = 31; bit >= 0; --bit) {
             const uint32_t trial = thr | (1u << bit);
-            int c = 0;
+            int c = 0;                                  // wave-wide count on the scalar unit: one compare per key
 #pragma unroll
-            for (int m = 0; m < PER_LANE; ++m) c += (key[m] >= trial) ? 1 : 0;   // trial >= 1: padding keys stay out
-            if (wave_sum(c) >= kj) thr = trial;
+            for (int m = 0; m < PER_LANE; ++m) c += (int)__popcll(__ballot(key[m] >= trial));   // trial >= 1: padding keys stay out
+            if (c >= kj) thr = trial;
         }
         int above = 0;
 #pragma unroll
-        for (int m = 0; m < PER_LANE; ++m) above += (key[m] > thr) ? 1 : 0;
-        int ties_left = kj - wave_sum(above);          // >= 1 by construction of thr
+        for (int m = 0; m < PER_LANE; ++m) above += (int)__popcll(__ballot(key[m] > thr));
+        int ties_left = kj - above;                    // >= 1 by construction of thr
 #pragma unroll
         for (int m = 0; m < PER_LANE; ++m) {
             if (m * 64 >= n_cand) break;                // wave-uniform
