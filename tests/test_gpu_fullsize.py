@@ -151,3 +151,18 @@ def test_c5_two_fused_layers_budget_sweep():
         e = {b: float((errs[b].float() - dense.float()).abs().mean()) for b in errs}
         print("  mean |sparse - dense| by budget:", e, flush=True)
         assert e[4096] <= e[1024] <= e[512]
+
+
+def test_max_blocks_8192_b16():
+    """The largest block count the estimate / select steps accept (8192 blocks: 128K tokens, block 16), at a
+    reduced head count so that the checker finishes in seconds; attention runs the any-block-size path."""
+    w = synth.Workload("max_blocks_128k_b16", 1, 4, 2, 128, 131072, 512, 16, 128, 2, seed=1240)
+    q, k, v = synth.make_qkv(w, threads=THREADS)
+    qd, kd, vd, S, idx, cnt, out, lse = run_layer(w, q, k, v)
+    assert torch.isfinite(out.float()).all() and torch.isfinite(lse).all()
+    check_list_structure(w, idx, cnt)
+    check_heads(w, q, k, v, S, idx, cnt, out, [(0, 0), (0, 3)], segments=[0, 1, 9, 255])
+    # the estimate with the softmax over visible blocks only, for one head
+    S1 = H.gpu_estimate(w, qd, kd, softmax_domain=1)
+    S1_o = O.estimate(synth.to_f64(q[:, 2:3]), synth.to_f64(k[:, 1:2]), w.segment_size, w.block_size, softmax_domain=1)
+    np.testing.assert_allclose(S1[0, 2].cpu().numpy(), S1_o[0, 0], rtol=3e-4, atol=1e-30)
