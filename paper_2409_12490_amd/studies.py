@@ -1,5 +1,5 @@
 #!/usr/bin/env python3
-"""Four measurements beyond the headline benchmark, on one MI355X, printed as JSON lines.
+"""Five measurements beyond the headline benchmark, on one MI355X, printed as JSON lines.
 
 ``python -m paper_2409_12490_amd.studies fusion``
     Cost of the layer-fusion line of Algorithm 1 (S = alpha*S + (1-alpha)*S'): the estimate step at 128K with and
@@ -26,6 +26,14 @@
     extension the paper does not describe: latency of select + sparse attention and the change of the output error
     (against the library's dense kernel) at 128K, for the budget of the benchmark and for a budget G times larger
     (the union of G per-head lists is at most that long).
+
+``python -m paper_2409_12490_amd.studies clock``
+    Model kernels of the bf16 attention key loop (csrc/loop_model.hip, built into libcp_loop_model.so): a stream of
+    nothing but MFMAs, and the loop's own mix of MFMAs, LDS fragment reads, softmax arithmetic and tile barrier without
+    global traffic, each with constant and with pseudo-random operand bits.  Prints microseconds per 64-key step of a
+    compute unit and the MFMA rate.  Run under ``rocprofv3 --pmc GRBM_GUI_ACTIVE --kernel-trace`` the counter (summed
+    over the 8 XCDs) divided by 8 and by the kernel's duration is the clock the chip sustained: the cycle counts do not
+    depend on the operand bits, the clock does.
 
 Inputs are the seeded synthetic Q/K/V of ``synth``; every latency and every block list comes from the HIP library
 through the C ABI.
@@ -200,8 +208,33 @@ def shared(dev: str = "cuda:0") -> None:
                               "mean_listed_blocks": round(float(cnt.float().mean()), 2)}), flush=True)
 
 
+def clock(steps: int = 20000) -> None:
+    import ctypes
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcp_loop_model.so")
+    if not os.path.exists(path):
+        raise FileNotFoundError(f"{path} not built: run `python -m paper_2409_12490_amd.build`")
+    lib = ctypes.CDLL(path)
+    lib.cp_loop_model.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_float)]
+    lib.cp_loop_model.restype = ctypes.c_int
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    names = {0: "MFMA only", 1: "attention loop model, row sums by additions", 2: "attention loop model, row sums by v_dot2c"}
+    for rep in range(2):                                      # the second pass runs on a warm chip
+        for kind in (0, 1, 2):
+            for rnd in (0, 1):
+                ms = ctypes.c_float(0.0)
+                st = lib.cp_loop_model(kind, rnd, steps, ctypes.byref(ms))
+                if st != 0:
+                    raise RuntimeError(f"cp_loop_model({kind}, {rnd}) failed with status {st}")
+                us = ms.value * 1e3 / steps
+                flop = 4.0 * 128 * 256 * 64 * cus                  # one 256-row x 64-key step on every compute unit
+                print(json.dumps({"study": "clock", "pass": rep, "kernel": names[kind],
+                                  "operand_bits": "random" if rnd else "constant", "us_per_step": round(us, 4),
+                                  "mfma_pflops": round(flop / (us * 1e-6) / 1e15, 3), "launch_ms": round(ms.value, 3)}),
+                      flush=True)
+
+
 def main(argv) -> int:
-    if len(argv) != 2 or argv[1] not in ("fusion", "length", "locality", "shared"):
+    if len(argv) != 2 or argv[1] not in ("fusion", "length", "locality", "shared", "clock"):
         print(__doc__)
         return 2
     if not torch.cuda.is_available():
@@ -209,7 +242,7 @@ def main(argv) -> int:
         return 2
     B.load()
     torch.cuda.set_device(0)
-    {"fusion": fusion, "length": length, "locality": locality, "shared": shared}[argv[1]]()
+    {"fusion": fusion, "length": length, "locality": locality, "shared": shared, "clock": clock}[argv[1]]()
     return 0
 
 
