@@ -50,6 +50,7 @@ constexpr int kTokOff = 0;                            // [NBUF][TK] token positi
 constexpr int kVOff = 1024;                           // [NBUF] V tiles
 constexpr int kKOff = kVOff + NBUF * kTileBytes;      // [NBUF] K tiles
 constexpr int kListOff = kKOff + NBUF * kTileBytes;   // the segment's block list (sparse only)
+constexpr float kLazyLog2 = 8.0f;        // see the softmax phase: how far a row's max may outgrow its reference point
 constexpr int kOutPitch = 272;                        // epilogue staging: one output row + 16 B, in bytes
 static_assert(kListOff + kMaxListBf16 * 4 <= 160 * 1024, "LDS budget");
 static_assert(8 * WQ * kOutPitch <= 2 * NBUF * kTileBytes, "epilogue staging reuses the tile rings");
@@ -309,6 +310,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
         for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
     const float c = a.scale_log2e;
+    const float lazy_raw = kLazyLog2 / c;                        // the same margin in units of the raw logits
 
     // ---- the three phases ---------------------------------------------------------------------
     // LDS fragments are read in groups of four (4 MFMAs each) into two alternating register groups, one
@@ -433,7 +435,10 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
             my = fmaxf(fmaxf(s[1][r], s[1][r + 1]), my);
         }
         mx = half_max(fmaxf(mx, my));
-        const float m_new = fmaxf(m_run, mx);
+        // The reference point of a row moves only when the row's max has outgrown it by more than 2^kLazyLog2 in the
+        // exponent: until then P is computed against the old reference (P <= 2^kLazyLog2, exact in fp32 and well inside
+        // bf16's range; O, l and the final O / l all carry the same factor), and O needs no rescaling.
+        const float m_new = (mx > m_run + lazy_raw) ? mx : m_run;
         const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
         const float alpha = __builtin_amdgcn_exp2f((m_run - m_safe) * c);
         const float ms = m_safe * c;
