@@ -39,7 +39,8 @@ enum {
     CP_OK = 0,
     CP_ERR_NULL = -1,        /* a required pointer is NULL */
     CP_ERR_SHAPE = -2,       /* non-positive size, n_q_heads % n_kv_heads != 0, block_size does not divide segment_size */
-    CP_ERR_UNSUPPORTED = -3, /* head_dim != 128, unknown dtype or softmax_domain, n2 > 8192, list longer than the API allows */
+    CP_ERR_UNSUPPORTED = -3, /* head_dim != 128, unknown dtype or softmax_domain, n2 > 8192, list longer than the API allows,
+                                bf16 estimate with batch * n_q_heads > 65535 */
     CP_ERR_ALIGN = -4,       /* a pointer is not 16-byte aligned or a stride is not a multiple of 8 elements */
     CP_ERR_WORKSPACE = -5,   /* workspace smaller than critiprefill_workspace_bytes() */
     CP_ERR_LAUNCH = -6       /* the HIP runtime refused a launch */

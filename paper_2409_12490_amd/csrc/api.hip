@@ -99,6 +99,7 @@ int critiprefill_estimate(const critiprefill_params* p, const void* q, const voi
     if (e != CP_OK) return e;
     if (!q || !k || !scores || !workspace) return CP_ERR_NULL;
     if (sh.n2 > kMaxBlocks) return CP_ERR_UNSUPPORTED;
+    if (sh.dtype == CP_DTYPE_BF16 && (long long)sh.batch * sh.hq > 65535) return CP_ERR_UNSUPPORTED;   // grid.z of the score kernels
     if (!aligned16(q) || !aligned16(k) || !aligned16(scores) || !aligned16(workspace) ||
         (prev_scores && !aligned16(prev_scores)))
         return CP_ERR_ALIGN;

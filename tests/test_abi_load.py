@@ -69,7 +69,16 @@ def test_bad_shapes_are_rejected_before_launch(kw, code):
     assert lib.critiprefill_sparse_attn(ctypes.byref(p), fake, fake, fake, fake, fake, fake, None, None) == code
     assert lib.critiprefill_dense_causal_attn(ctypes.byref(p), fake, fake, fake, fake, None, None) == code
     assert B.critiprefill_list_len(p) == code
+    assert lib.critiprefill_select_shared(ctypes.byref(p), fake, fake, fake, None) == code
+    assert lib.critiprefill_sparse_attn_shared(ctypes.byref(p), fake, fake, fake, fake, fake, fake, None, None) == code
     assert B.critiprefill_workspace_bytes(p) == 0
+
+
+def test_bf16_estimate_rejects_more_than_65535_batch_heads():
+    lib = B.load()
+    p = _params(batch=16384)                # 16384 * 4 query heads
+    fake = ctypes.c_void_p(0x1000)
+    assert lib.critiprefill_estimate(ctypes.byref(p), fake, fake, None, fake, fake, 1 << 40, None) == -3
 
 
 def test_null_alignment_and_workspace_errors():
