@@ -23,6 +23,7 @@ SMALL = [
     ("bf16_b16_small_seg",    1, 2, 2,  777,  64,  16, 5, 2, "bf16"),
     ("bf16_b128_seg512",      1, 2, 1, 2048, 512, 128, 3, 1, "bf16"),
     ("bf16_seg_eq_block",     1, 2, 2,  640,  64,  64, 2, 1, "bf16"),
+    ("bf16_many_segments",    1, 2, 1, 8400,  64,  16, 6, 1, "bf16"),   # 132 segments, 525 blocks: several score chunks
     ("fp32_c1_like",          1, 2, 1, 1000, 128,  32, 8, 0, "fp32"),
     ("fp32_b8",               1, 3, 3,  300,  32,   8, 4, 1, "fp32"),
 ]
@@ -60,6 +61,22 @@ def test_estimate_scores(case):
     w2 = w.replace(alpha=0.25)
     S_g = H.gpu_estimate(w2, q.to(DEV), k.to(DEV), prev=torch.from_numpy(prev).to(DEV)).cpu().numpy()
     np.testing.assert_allclose(S_g, S_f, rtol=2e-4, atol=1e-30)
+
+
+def test_estimate_fusion_in_place():
+    """prev_scores may alias scores (the fused score of the previous layer is overwritten by this layer's)."""
+    case = [c for c in SMALL if c[0] == "bf16_many_segments"][0]
+    w, q, k, v = make(case)
+    w = w.replace(alpha=0.5)
+    qf, kf = synth.to_f64(q), synth.to_f64(k)
+    prev = np.random.default_rng(3).random((w.batch, w.n_q_heads, w.n_segments, w.n_blocks)).astype(np.float32)
+    S_o = O.estimate(qf, kf, w.segment_size, w.block_size, prev_scores=prev.astype(np.float64), alpha=0.5)
+    p = H.params_for(w, q.to(DEV), k.to(DEV))
+    S = torch.from_numpy(prev).to(DEV)
+    ws = B.alloc_workspace(p)
+    B.critiprefill_estimate(p, q.to(DEV), k.to(DEV), S, S, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(S.cpu().numpy(), S_o, rtol=2e-4, atol=1e-30)
 
 
 @pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
