@@ -249,6 +249,8 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
                 *LDS_PTR(int, lds0 + kTokOff + slot * TK * 4 + (32 * i + 4 * wave + r4) * 4) = tokv[i];
         }
     };
+    int pre_ent = 0; bool early = false;                   // the list entry of the next walk step, fetched at the start of the tile step
+    auto prefetch_entry = [&]() { if (FAST && !DENSE) { pre_ent = *LDS_PTR(const int, lds0 + kListOff + min(walk_e, max(count - 1, 0)) * 4); early = true; } };
     auto next_base = [&]() -> int {                          // MODE 1/2: first token of the next tile in order, -1 past the end
         int base = -1;
         if (DENSE) {
@@ -256,7 +258,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
             ++dense_tile;
         } else {
             if (walk_e < count)
-                base = __builtin_amdgcn_readfirstlane(*LDS_PTR(const int, lds0 + kListOff + walk_e * 4)) * a.b + walk_off;
+                base = __builtin_amdgcn_readfirstlane(early ? pre_ent : *LDS_PTR(const int, lds0 + kListOff + walk_e * 4)) * a.b + walk_off;
             walk_off += TK;
             if (walk_off >= a.b) { walk_off = 0; ++walk_e; }
         }
@@ -522,6 +524,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
         if (act) read_kg(0, 0);
         for (int t = 0; t < ntiles; ++t) {
             const int slot = t & 3, nslot = (t + 1) & 3;
+            prefetch_entry();
             __builtin_amdgcn_s_setprio(3);                               // matrix phase: its MFMAs go ahead of the partner's VALU work
             if (have_p && act) mm_both(s, pf);
             else if (act) qk(s);
@@ -547,6 +550,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
         next_k_slot();
         for (int t = 0; t < ntiles; ++t) {
             const int slot = t & 3, nslot = (t + 1) & 3;
+            prefetch_entry();
             const bool act_next = have_s && (t + 1 < ntiles) && tile_active(nslot, nb[1]);
             if (have_s) {
                 read_vg(0, 0);                                       // first group of the matrix phase below
