@@ -179,6 +179,34 @@ def test_dense_causal_attention(case):
     assert H.max_abs(lse.cpu().numpy(), lse_ref) <= (2e-2 if w.dtype == "bf16" else 1e-4)
 
 
+@pytest.mark.parametrize("gain", [6.0, 0.05], ids=["peaked", "flat"])
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_attention_peaked_and_flat_logits(dtype, gain):
+    """Logits far from the unit scale of the other cases.  gain 6 (q and k both times 6: logits 36 times
+    larger, every row's softmax dominated by one or two keys, the running maximum moving again and again while
+    the row walks its tiles); gain 0.05 (all weights nearly equal).  Sparse and dense kernels against the checker."""
+    w = H.small_workload("gain", 1, 4, 2, 2500, 256, 64, 6, 1, dtype=dtype, unit_variance=True)
+    q, k, v = synth.make_qkv(w, threads=2)
+    q, k = (q.float() * gain).to(q.dtype), (k.float() * gain).to(k.dtype)
+    print("dtype", dtype, "gain", gain, flush=True)
+    qf, kf, vf = synth.to_f64(q), synth.to_f64(k), synth.to_f64(v)
+    _, _, idx_o, cnt_o = oracle_lists(w, q, k)
+    tol_lse = 2e-2 if dtype == "bf16" else 1e-4 * max(1.0, gain * gain)
+    o_ref, lse_ref = O.sparse_attention(qf, kf, vf, idx_o, cnt_o, w.segment_size, w.block_size)
+    out, lse = H.gpu_sparse(w, q.to(DEV), k.to(DEV), v.to(DEV),
+                            torch.from_numpy(idx_o).to(DEV), torch.from_numpy(cnt_o).to(DEV))
+    err = H.max_abs(out.float().cpu().numpy(), o_ref)
+    print("sparse max abs err", err, "lse err", H.max_abs(lse.cpu().numpy(), lse_ref), flush=True)
+    assert err <= H.TOL_OUT[dtype]
+    assert H.max_abs(lse.cpu().numpy(), lse_ref) <= tol_lse
+    d_ref, dlse_ref = O.dense_causal_attention(qf, kf, vf)
+    dout, dlse = H.gpu_dense(w, q.to(DEV), k.to(DEV), v.to(DEV))
+    err = H.max_abs(dout.float().cpu().numpy(), d_ref)
+    print("dense max abs err", err, "lse err", H.max_abs(dlse.cpu().numpy(), dlse_ref), flush=True)
+    assert err <= H.TOL_OUT[dtype]
+    assert H.max_abs(dlse.cpu().numpy(), dlse_ref) <= tol_lse
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
 def test_full_budget_reproduces_dense_on_gpu(dtype):
     w = H.small_workload("fullbudget", 1, 2, 1, 900, 128, 32, 64, 0, dtype=dtype, unit_variance=(dtype == "bf16"))
