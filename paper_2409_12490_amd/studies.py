@@ -34,6 +34,9 @@
     compute unit and the MFMA rate.  Run under ``rocprofv3 --pmc GRBM_GUI_ACTIVE --kernel-trace`` the counter (summed
     over the 8 XCDs) divided by 8 and by the kernel's duration is the clock the chip sustained: the cycle counts do not
     depend on the operand bits, the clock does.
+    Then the library's own dense and block-sparse attention kernels at 64K tokens on pseudo-random and on constant
+    Q/K/V (same launches, same list lengths, same instruction stream), each run for a few seconds while the shader
+    clock is read from ``rocm-smi --showclocks`` (omitted when that tool is not there).
 
 Inputs are the seeded synthetic Q/K/V of ``synth``; every latency and every block list comes from the HIP library
 through the C ABI.
@@ -233,6 +236,85 @@ def clock(steps: int = 20000) -> None:
                       flush=True)
 
 
+def _sclk_mhz():
+    """Current shader clock of GPU 0 according to rocm-smi, or None."""
+    import re
+    import shutil
+    import subprocess
+    exe = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
+    try:
+        r = subprocess.run([exe, "-d", "0", "--showclocks", "--json"], capture_output=True, text=True, timeout=20)
+        m = re.search(r'"sclk clock speed:"\s*:\s*"\((\d+)Mhz\)"', r.stdout)
+        return int(m.group(1)) if m else None
+    except (OSError, subprocess.SubprocessError):
+        return None
+
+
+def clock_library_kernels(dev: str = "cuda:0", seq_len: int = 65536, seconds: float = 4.0) -> None:
+    import threading
+    import time
+    w = synth.WORKLOADS["c3_llama3_8b_128k"].replace(seq_len=seq_len)
+    d, s, b, r, n = w.head_dim, w.segment_size, w.block_size, w.blocks_per_segment, w.seq_len
+    for bits in ("random", "constant"):
+        if bits == "random":
+            g = torch.Generator(device=dev)
+            g.manual_seed(w.seed)
+            q, k, v = (torch.randn(w.batch, h, n, d, device=dev, generator=g).to(torch.bfloat16)
+                       for h in (w.n_q_heads, w.n_kv_heads, w.n_kv_heads))
+        else:
+            q, k, v = (torch.full((w.batch, h, n, d), 0.5, device=dev, dtype=torch.bfloat16)
+                       for h in (w.n_q_heads, w.n_kv_heads, w.n_kv_heads))
+        out = torch.empty_like(q)
+        p = B.make_params(q, k, s, b, w.budget_blocks, w.local_blocks, out=out)
+        S = B.alloc_scores(p, dev)
+        ws = B.alloc_workspace(p, dev)
+        idx, cnt = B.alloc_lists(p, dev)
+        B.critiprefill_estimate(p, q, k, None, S, ws)
+        B.critiprefill_select(p, S, idx, cnt)
+        torch.cuda.synchronize()
+        rows = w.batch * w.n_q_heads * w.n_segments
+        pairs = (int(cnt.to(torch.int64).sum().item()) - rows * r) * b * s + rows * (s * (s + 1) // 2)
+        kernels = {
+            "dense causal attention": (lambda: B.critiprefill_dense_causal_attn(p, q, k, v, out, None),
+                                       4.0 * d * w.batch * w.n_q_heads * (n * (n + 1) // 2), 2),
+            "block-sparse attention": (lambda: B.critiprefill_sparse_attn(p, q, k, v, idx, cnt, out, None),
+                                       4.0 * d * pairs, 20),
+        }
+        for name, (fn, flop, per_sync) in kernels.items():
+            fn()
+            torch.cuda.synchronize()
+            clocks, stop = [], threading.Event()
+
+            def sample():
+                while not stop.is_set():
+                    c = _sclk_mhz()
+                    if c is not None:
+                        clocks.append(c)
+                    time.sleep(0.25)
+
+            th = threading.Thread(target=sample)
+            th.start()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            launches, t0 = 0, time.time()
+            e0.record()
+            while time.time() - t0 < seconds:
+                for _ in range(per_sync):
+                    fn()
+                torch.cuda.synchronize()
+                launches += per_sync
+            e1.record()
+            torch.cuda.synchronize()
+            stop.set()
+            th.join()
+            ms = e0.elapsed_time(e1) / launches
+            clocks = sorted(clocks[1:])                      # the first sample may predate the ramp-up
+            print(json.dumps({"study": "clock", "kernel": name, "seq_len": n, "operand_bits": bits,
+                              "ms_per_launch": round(ms, 4), "pflops": round(flop / (ms * 1e-3) / 1e15, 3),
+                              "sclk_mhz_median": clocks[len(clocks) // 2] if clocks else None,
+                              "sclk_samples": len(clocks)}), flush=True)
+        del q, k, v, out, S, ws, idx, cnt
+
+
 def main(argv) -> int:
     if len(argv) != 2 or argv[1] not in ("fusion", "length", "locality", "shared", "clock"):
         print(__doc__)
@@ -243,6 +325,8 @@ def main(argv) -> int:
     B.load()
     torch.cuda.set_device(0)
     {"fusion": fusion, "length": length, "locality": locality, "shared": shared, "clock": clock}[argv[1]]()
+    if argv[1] == "clock":
+        clock_library_kernels()
     return 0
 
 
