@@ -9,8 +9,6 @@
 namespace cp {
 namespace {
 
-constexpr int kWave = 64;
-
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 // both inputs hold exact bf16 values, so taking the upper halves loses nothing

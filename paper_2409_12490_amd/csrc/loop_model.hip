@@ -150,13 +150,15 @@ hipError_t run_one(int steps, float* ms) {
     if ((e = hipEventCreate(&e0)) != hipSuccess) return e;
     if ((e = hipEventCreate(&e1)) != hipSuccess) return e;
     hipLaunchKernelGGL((loop_model_kernel<KIND, RANDOM>), dim3(cus), dim3(512), 65536, 0, sink, 16);   // warm-up
-    hipEventRecord(e0, 0);
+    e = hipEventRecord(e0, 0);
     hipLaunchKernelGGL((loop_model_kernel<KIND, RANDOM>), dim3(cus), dim3(512), 65536, 0, sink, steps);
-    hipEventRecord(e1, 0);
-    e = hipEventSynchronize(e1);
+    if (e == hipSuccess) e = hipEventRecord(e1, 0);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
     if (e == hipSuccess) e = hipEventElapsedTime(ms, e0, e1);
-    hipEventDestroy(e0); hipEventDestroy(e1);
-    return e == hipSuccess ? hipGetLastError() : e;
+    const hipError_t d0 = hipEventDestroy(e0), d1 = hipEventDestroy(e1);
+    if (e == hipSuccess) e = hipGetLastError();
+    if (e == hipSuccess) e = d0 != hipSuccess ? d0 : d1;
+    return e;
 }
 
 }  // namespace
