@@ -303,20 +303,3 @@ def sparse_attention(q, k, v, block_idx, block_cnt, segment_size, block_size,
         return out, lse, probs
     return out, lse
 
-
-def attended_pairs(block_idx, block_cnt, seq_len, segment_size, block_size):
-    """Number of (query, key) pairs with key <= query that the lists visit, per [B,H]."""
-    B, H, n1, _ = block_idx.shape
-    pairs = np.zeros((B, H), dtype=np.int64)
-    for b in range(B):
-        for h in range(H):
-            for j in range(n1):
-                t0, t1 = j * segment_size, min(seq_len, (j + 1) * segment_size)
-                for i in block_idx[b, h, j, :block_cnt[b, h, j]]:
-                    u0, u1 = i * block_size, min(seq_len, (i + 1) * block_size)
-                    if u1 - 1 <= t0:
-                        pairs[b, h] += (t1 - t0) * (u1 - u0)
-                    else:
-                        for t in range(t0, t1):
-                            pairs[b, h] += max(0, min(u1, t + 1) - u0)
-    return pairs

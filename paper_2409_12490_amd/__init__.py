@@ -1,7 +1,7 @@
 """MI355X-native CritiPrefill prefill-attention path.
 
-``critiprefill`` (this package's binding module) marshals arguments into the C ABI of
-``libcritiprefill.so`` (hand-written HIP kernels for gfx950); ``synth`` draws the seeded
-synthetic inputs; ``build`` compiles the library.  Importing the package loads nothing.
+``binding`` marshals arguments into the C ABI of ``libcritiprefill.so`` (hand-written HIP kernels for
+gfx950); ``synth`` draws the seeded synthetic inputs; ``build`` compiles the library; ``studies`` holds
+measurements beyond the headline benchmark.  Importing the package loads nothing.
 """
-__all__ = ["binding", "synth", "build"]
+__all__ = ["binding", "synth", "build", "studies"]

@@ -9,7 +9,6 @@ from concurrent.futures import ThreadPoolExecutor
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libcritiprefill.so")
-MODEL_LIB = os.path.join(PKG, "libcp_loop_model.so")    # diagnostic model kernels of the attention loop (studies clock)
 SOURCES = ["api.hip", "estimate.hip", "select.hip", "attn_fp32.hip", "attn_bf16.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -17,8 +16,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
 # attn_bf16: MFMA results stay in architectural VGPRs (S^T feeds the softmax VALU code directly; the
 # operands that only MFMA touches live in AGPRs), and fmaxf needs no NaN-quieting pre-pass (the kernel
 # never produces NaN: masked logits are -inf and the running max is guarded).
-EXTRA = {"attn_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1", "-fno-honor-nans", "-mno-amdgpu-ieee"],
-         "loop_model.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1", "-fno-honor-nans", "-mno-amdgpu-ieee"]}
+EXTRA = {"attn_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1", "-fno-honor-nans", "-mno-amdgpu-ieee"]}
 
 
 def _compile(src: str, objdir: str) -> str:
@@ -41,16 +39,8 @@ def build(verbose: bool = False) -> str:
     if r.returncode != 0:
         sys.stderr.write(r.stdout + r.stderr)
         raise RuntimeError("link failed")
-    # the diagnostic library: one source, its own .so, so that the product library exports the C ABI only
-    obj = _compile("loop_model.hip", objdir)
-    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", MODEL_LIB, obj],
-                       capture_output=True, text=True)
-    if r.returncode != 0:
-        sys.stderr.write(r.stdout + r.stderr)
-        raise RuntimeError("link failed")
     if verbose:
         print("built", LIB)
-        print("built", MODEL_LIB)
     return LIB
 
 

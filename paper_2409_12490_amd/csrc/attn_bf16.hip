@@ -79,7 +79,7 @@ __device__ __forceinline__ void pin(const bf16x8& v) { asm volatile("" ::"v"(v))
 // before the tile barrier.
 __device__ __forceinline__ void dma16(const void* sbase, unsigned voff, unsigned lds_base) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 __device__ __forceinline__ const uint16_t* uniform_ptr(const uint16_t* p) {   // into SGPRs
@@ -164,7 +164,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
     if (!DENSE) {
         const long long lrow = a.shared_lists ? ((long long)bb * a.hkv + g) * a.n1 + j : ((long long)bb * a.hq + h) * a.n1 + j;
         const int32_t* list = a.idx + lrow * a.list_len;
-        count = a.cnt[lrow];
+        count = min(max(a.cnt[lrow], 0), a.list_len);             // a bad count must not run past the list's LDS region
         for (int x = tid; x < count; x += 512) *LDS_PTR(int, lds0 + kListOff + x * 4) = list[x];
     }
     __syncthreads();
@@ -235,7 +235,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int tok = ent[i] * a.b + eoff[i];
-            const bool valid = ent[i] >= 0 && tok < a.n;
+            const bool valid = ent[i] >= 0 && (unsigned)tok < (unsigned)a.n;   // also rejects entries whose token index wrapped
             const unsigned base = __umul24(valid ? (unsigned)tok : 0u, tok_bytes);  // invalid rows read token 0, masked later
             koff[i] = base + kch * 16;
             voff[i] = base + vch * 16;
@@ -265,7 +265,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
         return base;
     };
     auto base_offsets = [&](int base) {                      // MODE 1/2: offsets of the tile that starts at token base
-        if (base >= 0 && base + TK <= a.n) {                 // uniform: the whole tile exists
+        if (base >= 0 && base <= a.n - TK) {                 // uniform: the whole tile exists
             const unsigned sb = (unsigned)base * tok_bytes;
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
@@ -275,7 +275,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 const int tok = base + 32 * i + 4 * wave + r4;
-                const bool valid = base >= 0 && tok < a.n;
+                const bool valid = base >= 0 && (unsigned)tok < (unsigned)a.n;
                 const unsigned sb = __umul24(valid ? (unsigned)tok : 0u, tok_bytes);
                 koff[i] = sb + kch * 16; voff[i] = sb + vch * 16;
             }

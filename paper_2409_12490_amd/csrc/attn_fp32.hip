@@ -52,7 +52,7 @@ __global__ __launch_bounds__(256) void attn_fp32_kernel(Args32 a) {
     if (!DENSE) {
         const long long lrow = a.shared_lists ? ((long long)bb * a.hkv + g) * a.n1 + j : ((long long)bb * a.hq + h) * a.n1 + j;
         list = a.idx + lrow * a.list_len;
-        count = a.cnt[lrow];
+        count = min(max(a.cnt[lrow], 0), a.list_len);
     }
     const long long total = DENSE ? (long long)q_last + 1 : (long long)count * a.b;   // virtual key positions
     const int ntiles = (int)((total + TK - 1) / TK);
@@ -75,8 +75,10 @@ __global__ __launch_bounds__(256) void attn_fp32_kernel(Args32 a) {
             else {
                 const int e = (int)(p / a.b);
                 valid = e < count;
-                tok = valid ? list[e] * a.b + (int)(p - (long long)e * a.b) : 0;
-                valid = valid && tok < a.n;
+                const long long blk = valid ? list[e] : 0;
+                const long long tk = blk * a.b + (p - (long long)e * a.b);
+                valid = valid && blk >= 0 && tk < a.n;             // entries outside the sequence are masked rows
+                tok = valid ? (int)tk : 0;
             }
             float4 kv = make_float4(0.f, 0.f, 0.f, 0.f), vv = kv;
             if (valid) {

@@ -157,7 +157,7 @@ __global__ __launch_bounds__(256) void pool_fp32_kernel(PoolArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// score: one workgroup per (batch, head, segment) row of S.
+// score, fp32 (correctness configuration): one workgroup per (batch, head, segment) row of S, plain fp32 FMA.
 // ---------------------------------------------------------------------------------------------
 struct ScoreArgs {
     const void* qrep; const void* krep; const float* prev; float* scores;
@@ -186,7 +186,6 @@ __device__ __forceinline__ float block_reduce_sum(float v, float* red) {
     return (red[0] + red[1]) + (red[2] + red[3]);
 }
 
-template <bool BF16>
 __global__ __launch_bounds__(256) void score_valu_kernel(ScoreArgs a) {
     extern __shared__ float smem[];
     float* qr = smem;                 // [2][128]
@@ -197,47 +196,22 @@ __global__ __launch_bounds__(256) void score_valu_kernel(ScoreArgs a) {
     const long long qrow = ((long long)bb * a.hq + h) * a.n1 + j;
     const int g = h / (a.hq / a.hkv);
     const long long kbase = ((long long)bb * a.hkv + g) * a.n2;
-    if (BF16) {
-        const uint16_t* src = (const uint16_t*)a.qrep + qrow * 2 * kHeadDim;
-        qr[tid] = __uint_as_float((uint32_t)src[tid] << 16);
-    } else {
-        qr[tid] = ((const float*)a.qrep)[qrow * 2 * kHeadDim + tid];
-    }
+    qr[tid] = ((const float*)a.qrep)[qrow * 2 * kHeadDim + tid];
     __syncthreads();
     const int vis = min(a.n2, (j + 1) * a.r);               // first block wholly after the segment
     const int dom = a.domain == 0 ? a.n2 : vis;
     for (int i = tid; i < a.n2; i += 256) {
         float zz[4] = {0.f, 0.f, 0.f, 0.f};
-        if (BF16) {
-            const uint4* km = (const uint4*)((const uint16_t*)a.krep + (kbase + i) * 2 * kHeadDim);
+        const float4* km = (const float4*)((const float*)a.krep + (kbase + i) * 2 * kHeadDim);
 #pragma unroll 4
-            for (int c = 0; c < 16; ++c) {
-                const uint4 hi4 = km[c], lo4 = km[16 + c];
-                const uint32_t wh[4] = {hi4.x, hi4.y, hi4.z, hi4.w}, wl[4] = {lo4.x, lo4.y, lo4.z, lo4.w};
+        for (int c = 0; c < 32; ++c) {
+            const float4 hi4 = km[c], lo4 = km[32 + c];
+            const float kh[4] = {hi4.x, hi4.y, hi4.z, hi4.w}, kl[4] = {lo4.x, lo4.y, lo4.z, lo4.w};
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int ch = c * 8 + 2 * e;
-                    const float kh0 = bf16_lo(wh[e]), kh1 = bf16_hi(wh[e]);
-                    const float kl0 = bf16_lo(wl[e]), kl1 = bf16_hi(wl[e]);
-                    const float qh0 = qr[ch], qh1 = qr[ch + 1], ql0 = qr[kHeadDim + ch], ql1 = qr[kHeadDim + ch + 1];
-                    zz[0] = fmaf(qh0, kh0, zz[0]); zz[0] = fmaf(qh1, kh1, zz[0]);
-                    zz[1] = fmaf(qh0, kl0, zz[1]); zz[1] = fmaf(qh1, kl1, zz[1]);
-                    zz[2] = fmaf(ql0, kh0, zz[2]); zz[2] = fmaf(ql1, kh1, zz[2]);
-                    zz[3] = fmaf(ql0, kl0, zz[3]); zz[3] = fmaf(ql1, kl1, zz[3]);
-                }
-            }
-        } else {
-            const float4* km = (const float4*)((const float*)a.krep + (kbase + i) * 2 * kHeadDim);
-#pragma unroll 4
-            for (int c = 0; c < 32; ++c) {
-                const float4 hi4 = km[c], lo4 = km[32 + c];
-                const float kh[4] = {hi4.x, hi4.y, hi4.z, hi4.w}, kl[4] = {lo4.x, lo4.y, lo4.z, lo4.w};
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float qh = qr[c * 4 + e], ql = qr[kHeadDim + c * 4 + e];
-                    zz[0] = fmaf(qh, kh[e], zz[0]); zz[1] = fmaf(qh, kl[e], zz[1]);
-                    zz[2] = fmaf(ql, kh[e], zz[2]); zz[3] = fmaf(ql, kl[e], zz[3]);
-                }
+            for (int e = 0; e < 4; ++e) {
+                const float qh = qr[c * 4 + e], ql = qr[kHeadDim + c * 4 + e];
+                zz[0] = fmaf(qh, kh[e], zz[0]); zz[1] = fmaf(qh, kl[e], zz[1]);
+                zz[2] = fmaf(ql, kh[e], zz[2]); zz[3] = fmaf(ql, kl[e], zz[3]);
             }
         }
         const bool in_dom = i < dom;
@@ -378,7 +352,7 @@ __device__ __forceinline__ void score_load_piece(const ScoreArgs& a, const Score
         const unsigned dst =
             __builtin_amdgcn_readfirstlane(c.lds0 + (p & 1) * kPieceBytes + 1024u * (kPerWave * c.wave + x));
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(voff), "s"(sbase)
-                     : "memory");
+                     : "memory", "m0");
     }
 }
 // every load of this wave has landed, every wave has arrived (and is done with the buffer that is filled next)
@@ -641,12 +615,12 @@ hipError_t launch_score(const Shape& sh, const void* qrep, const void* krep, con
     }
     const size_t smem = (2 * kHeadDim + 4 + 4 * (size_t)sh.n2) * sizeof(float);
     dim3 grid(sh.n1, sh.hq, sh.batch);
-    const void* fn = (const void*)score_valu_kernel<false>;
+    const void* fn = (const void*)score_valu_kernel;
     if (smem > 48 * 1024) {
         const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(score_valu_kernel<false>, grid, dim3(256), smem, st, a);
+    hipLaunchKernelGGL(score_valu_kernel, grid, dim3(256), smem, st, a);
     return hipGetLastError();
 }
 

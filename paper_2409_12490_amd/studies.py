@@ -1,5 +1,5 @@
 #!/usr/bin/env python3
-"""Five measurements beyond the headline benchmark, on one MI355X, printed as JSON lines.
+"""Four measurements beyond the headline benchmark, on one MI355X, printed as JSON lines.
 
 ``python -m paper_2409_12490_amd.studies fusion``
     Cost of the layer-fusion line of Algorithm 1 (S = alpha*S + (1-alpha)*S'): the estimate step at 128K with and
@@ -26,17 +26,6 @@
     extension the paper does not describe: latency of select + sparse attention and the change of the output error
     (against the library's dense kernel) at 128K, for the budget of the benchmark and for a budget G times larger
     (the union of G per-head lists is at most that long).
-
-``python -m paper_2409_12490_amd.studies clock``
-    Model kernels of the bf16 attention key loop (csrc/loop_model.hip, built into libcp_loop_model.so): a stream of
-    nothing but MFMAs, and the loop's own mix of MFMAs, LDS fragment reads, softmax arithmetic and tile barrier without
-    global traffic, each with constant and with pseudo-random operand bits.  Prints microseconds per 64-key step of a
-    compute unit and the MFMA rate.  Run under ``rocprofv3 --pmc GRBM_GUI_ACTIVE --kernel-trace`` the counter (summed
-    over the 8 XCDs) divided by 8 and by the kernel's duration is the clock the chip sustained: the cycle counts do not
-    depend on the operand bits, the clock does.
-    Then the library's own dense and block-sparse attention kernels at 64K tokens on pseudo-random and on constant
-    Q/K/V (same launches, same list lengths, same instruction stream), each run for a few seconds while the shader
-    clock is read from ``rocm-smi --showclocks`` (omitted when that tool is not there).
 
 Inputs are the seeded synthetic Q/K/V of ``synth``; every latency and every block list comes from the HIP library
 through the C ABI.
@@ -211,112 +200,8 @@ def shared(dev: str = "cuda:0") -> None:
                               "mean_listed_blocks": round(float(cnt.float().mean()), 2)}), flush=True)
 
 
-def clock(steps: int = 20000) -> None:
-    import ctypes
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcp_loop_model.so")
-    if not os.path.exists(path):
-        raise FileNotFoundError(f"{path} not built: run `python -m paper_2409_12490_amd.build`")
-    lib = ctypes.CDLL(path)
-    lib.cp_loop_model.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_float)]
-    lib.cp_loop_model.restype = ctypes.c_int
-    cus = torch.cuda.get_device_properties(0).multi_processor_count
-    names = {0: "MFMA only", 1: "attention loop model, row sums by additions", 2: "attention loop model, row sums by v_dot2c"}
-    for rep in range(2):                                      # the second pass runs on a warm chip
-        for kind in (0, 1, 2):
-            for rnd in (0, 1):
-                ms = ctypes.c_float(0.0)
-                st = lib.cp_loop_model(kind, rnd, steps, ctypes.byref(ms))
-                if st != 0:
-                    raise RuntimeError(f"cp_loop_model({kind}, {rnd}) failed with status {st}")
-                us = ms.value * 1e3 / steps
-                flop = 4.0 * 128 * 256 * 64 * cus                  # one 256-row x 64-key step on every compute unit
-                print(json.dumps({"study": "clock", "pass": rep, "kernel": names[kind],
-                                  "operand_bits": "random" if rnd else "constant", "us_per_step": round(us, 4),
-                                  "mfma_pflops": round(flop / (us * 1e-6) / 1e15, 3), "launch_ms": round(ms.value, 3)}),
-                      flush=True)
-
-
-def _sclk_mhz():
-    """Current shader clock of GPU 0 according to rocm-smi, or None."""
-    import re
-    import shutil
-    import subprocess
-    exe = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
-    try:
-        r = subprocess.run([exe, "-d", "0", "--showclocks", "--json"], capture_output=True, text=True, timeout=20)
-        m = re.search(r'"sclk clock speed:"\s*:\s*"\((\d+)Mhz\)"', r.stdout)
-        return int(m.group(1)) if m else None
-    except (OSError, subprocess.SubprocessError):
-        return None
-
-
-def clock_library_kernels(dev: str = "cuda:0", seq_len: int = 65536, seconds: float = 4.0) -> None:
-    import threading
-    import time
-    w = synth.WORKLOADS["c3_llama3_8b_128k"].replace(seq_len=seq_len)
-    d, s, b, r, n = w.head_dim, w.segment_size, w.block_size, w.blocks_per_segment, w.seq_len
-    for bits in ("random", "constant"):
-        if bits == "random":
-            g = torch.Generator(device=dev)
-            g.manual_seed(w.seed)
-            q, k, v = (torch.randn(w.batch, h, n, d, device=dev, generator=g).to(torch.bfloat16)
-                       for h in (w.n_q_heads, w.n_kv_heads, w.n_kv_heads))
-        else:
-            q, k, v = (torch.full((w.batch, h, n, d), 0.5, device=dev, dtype=torch.bfloat16)
-                       for h in (w.n_q_heads, w.n_kv_heads, w.n_kv_heads))
-        out = torch.empty_like(q)
-        p = B.make_params(q, k, s, b, w.budget_blocks, w.local_blocks, out=out)
-        S = B.alloc_scores(p, dev)
-        ws = B.alloc_workspace(p, dev)
-        idx, cnt = B.alloc_lists(p, dev)
-        B.critiprefill_estimate(p, q, k, None, S, ws)
-        B.critiprefill_select(p, S, idx, cnt)
-        torch.cuda.synchronize()
-        rows = w.batch * w.n_q_heads * w.n_segments
-        pairs = (int(cnt.to(torch.int64).sum().item()) - rows * r) * b * s + rows * (s * (s + 1) // 2)
-        kernels = {
-            "dense causal attention": (lambda: B.critiprefill_dense_causal_attn(p, q, k, v, out, None),
-                                       4.0 * d * w.batch * w.n_q_heads * (n * (n + 1) // 2), 2),
-            "block-sparse attention": (lambda: B.critiprefill_sparse_attn(p, q, k, v, idx, cnt, out, None),
-                                       4.0 * d * pairs, 20),
-        }
-        for name, (fn, flop, per_sync) in kernels.items():
-            fn()
-            torch.cuda.synchronize()
-            clocks, stop = [], threading.Event()
-
-            def sample():
-                while not stop.is_set():
-                    c = _sclk_mhz()
-                    if c is not None:
-                        clocks.append(c)
-                    time.sleep(0.25)
-
-            th = threading.Thread(target=sample)
-            th.start()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            launches, t0 = 0, time.time()
-            e0.record()
-            while time.time() - t0 < seconds:
-                for _ in range(per_sync):
-                    fn()
-                torch.cuda.synchronize()
-                launches += per_sync
-            e1.record()
-            torch.cuda.synchronize()
-            stop.set()
-            th.join()
-            ms = e0.elapsed_time(e1) / launches
-            clocks = sorted(clocks[1:])                      # the first sample may predate the ramp-up
-            print(json.dumps({"study": "clock", "kernel": name, "seq_len": n, "operand_bits": bits,
-                              "ms_per_launch": round(ms, 4), "pflops": round(flop / (ms * 1e-3) / 1e15, 3),
-                              "sclk_mhz_median": clocks[len(clocks) // 2] if clocks else None,
-                              "sclk_samples": len(clocks)}), flush=True)
-        del q, k, v, out, S, ws, idx, cnt
-
-
 def main(argv) -> int:
-    if len(argv) != 2 or argv[1] not in ("fusion", "length", "locality", "shared", "clock"):
+    if len(argv) != 2 or argv[1] not in ("fusion", "length", "locality", "shared"):
         print(__doc__)
         return 2
     if not torch.cuda.is_available():
@@ -324,9 +209,7 @@ def main(argv) -> int:
         return 2
     B.load()
     torch.cuda.set_device(0)
-    {"fusion": fusion, "length": length, "locality": locality, "shared": shared, "clock": clock}[argv[1]]()
-    if argv[1] == "clock":
-        clock_library_kernels()
+    {"fusion": fusion, "length": length, "locality": locality, "shared": shared}[argv[1]]()
     return 0
 
 

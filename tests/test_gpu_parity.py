@@ -52,10 +52,16 @@ def test_estimate_scores(case):
         S_o = O.estimate(qf, kf, w.segment_size, w.block_size, softmax_domain=domain)
         S_g = H.gpu_estimate(w, q.to(DEV), k.to(DEV), softmax_domain=domain).cpu().numpy()
         np.testing.assert_allclose(S_g, S_o, rtol=2e-4, atol=1e-30)
-    # literal listing (no 1/sqrt(d)) and layer fusion with alpha = 0.25
+    # another scale, then the listing taken literally (score_scale = 1.0: no 1/sqrt(d); logits of the max/min
+    # representatives reach the hundreds, so each softmax is nearly one-hot and most scores underflow to 0)
     S_o = O.estimate(qf, kf, w.segment_size, w.block_size, score_scale=0.05)
     S_g = H.gpu_estimate(w, q.to(DEV), k.to(DEV), score_scale=0.05).cpu().numpy()
     np.testing.assert_allclose(S_g, S_o, rtol=2e-4, atol=1e-30)
+    S_o = O.scores_in_decision_precision(O.estimate(qf, kf, w.segment_size, w.block_size, score_scale=1.0))
+    S_g = H.gpu_estimate(w, q.to(DEV), k.to(DEV), score_scale=1.0).cpu().numpy()
+    # a logit z carries an fp32 rounding error of about |z| 2^-23 (accumulation of 128 exact products), which
+    # the exponential turns into a relative error of the same size in the score: |z| up to ~1e3 -> ~2e-4
+    np.testing.assert_allclose(S_g, S_o, rtol=1e-3, atol=2e-38)
     prev = np.random.default_rng(0).random(S_o.shape).astype(np.float32)
     S_f = O.estimate(qf, kf, w.segment_size, w.block_size, prev_scores=prev.astype(np.float64), alpha=0.25)
     w2 = w.replace(alpha=0.25)
@@ -274,3 +280,54 @@ def test_c1_full_config():
     err = H.max_abs(dout.cpu().numpy(), d_ref)
     print("c1 dense max abs err", err, flush=True)
     assert err <= 1e-4
+
+
+@pytest.mark.parametrize("case", [("bad_b64", 1, 2, 1, 1024, 256, 64, 3, 1, "bf16"),
+                                  ("bad_b32", 1, 2, 1, 1024, 256, 32, 3, 1, "bf16"),
+                                  ("bad_fp32", 1, 2, 1, 512, 128, 32, 3, 1, "fp32")], ids=lambda c: c[0])
+def test_bad_device_side_lists_give_masked_rows(case):
+    """A caller bug in the lists must not become an out-of-bounds access: a count beyond the list length is
+    clamped, a negative count is an empty list, negative entries and entries past the last block are
+    blocks without tokens.  Every access of the kernels stays inside Q/K/V and the list row for such input
+    (counts are clamped to the row pitch, tokens are bounds-checked), so nothing here can fault."""
+    w, q, k, v = make(case)
+    print("case", case, flush=True)
+    _, _, idx_o, cnt_o = oracle_lists(w, q, k)
+    idx_bad, cnt_bad = idx_o.copy(), cnt_o.copy()
+    idx_ref, cnt_ref = idx_o.copy(), cnt_o.copy()
+    n2 = w.n_blocks
+    cnt_bad[0, 0, 1] = 1_000_000                                   # A: count far beyond the row: valid prefix, then -1 padding
+    idx_bad[0, 0, 2, :2] = [n2 + 5, n2 + 100]; cnt_bad[0, 0, 2] = 2   # B: blocks past the end of the sequence
+    cnt_ref[0, 0, 2] = 0
+    cnt_bad[0, 1, 1] = -3; cnt_ref[0, 1, 1] = 0                    # C: negative count
+    idx_bad[0, 1, 2, 0] = -4; cnt_bad[0, 1, 2] = 1; cnt_ref[0, 1, 2] = 0   # D: negative entry
+    idx_bad[0, 1, 3, :] = 1 << 30; cnt_bad[0, 1, 3] = 2            # E: entries whose token index overflows 32 bits
+    o_ref, lse_ref = O.sparse_attention(synth.to_f64(q), synth.to_f64(k), synth.to_f64(v), idx_ref, cnt_ref,
+                                        w.segment_size, w.block_size)
+    out, lse = H.gpu_sparse(w, q.to(DEV), k.to(DEV), v.to(DEV),
+                            torch.from_numpy(idx_bad).to(DEV), torch.from_numpy(cnt_bad).to(DEV))
+    got, got_lse = out.float().cpu().numpy(), lse.cpu().numpy()
+    assert np.isfinite(got).all()
+    s = w.segment_size
+    keep = np.ones(w.seq_len, bool); keep[3 * s:4 * s] = False     # row E of head 1: only "no fault, finite" is asked
+    assert H.max_abs(got[0, 0], o_ref[0, 0]) <= H.TOL_OUT[w.dtype]
+    assert H.max_abs(got[0, 1][keep], o_ref[0, 1][keep]) <= H.TOL_OUT[w.dtype]
+    for (h, j) in ((0, 2), (1, 1), (1, 2)):
+        assert (got[0, h, j * s:(j + 1) * s] == 0).all() and np.isneginf(got_lse[0, h, j * s:(j + 1) * s]).all()
+
+
+def test_run_twice_bit_identical():
+    """The whole path twice on the same inputs: every output identical bit for bit (no atomics, no
+    order-dependent reductions anywhere in the kernels)."""
+    case = [c for c in SMALL if c[0] == "bf16_many_segments"][0]
+    w, q, k, v = make(case)
+    qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
+    runs = []
+    for _ in range(2):
+        S = H.gpu_estimate(w, qd, kd)
+        idx, cnt = H.gpu_select(w, qd, kd, S)
+        out, lse = H.gpu_sparse(w, qd, kd, vd, idx, cnt)
+        dout, dlse = H.gpu_dense(w, qd, kd, vd)
+        runs.append((S, idx, cnt, out, lse, dout, dlse))
+    for a, b in zip(*runs):
+        assert torch.equal(a, b)

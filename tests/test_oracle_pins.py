@@ -375,15 +375,6 @@ def test_decision_precision_flushes_subnormals():
     assert y[0] == 0 and y[1] == 0 and y[2] > 0 and y[3] == np.float32(0.5)
 
 
-def test_attended_pairs_counts_causal_triangle():
-    n, s, b = 64, 16, 4
-    n1, r = n // s, s // b
-    idx = np.full((1, 1, n1, r), -1, np.int32); cnt = np.zeros((1, 1, n1), np.int32)
-    for j in range(n1):
-        idx[0, 0, j, :r] = np.arange(j * r, (j + 1) * r); cnt[0, 0, j] = r
-    assert O.attended_pairs(idx, cnt, n, s, b)[0, 0] == n1 * s * (s + 1) // 2
-
-
 def test_shared_group_scores_bruteforce_and_special_cases():
     """The shared-list extension: element by element against python loops; one head per group is the
     identity; a list chosen from the group maximum contains each member head's single best candidate."""
