@@ -83,6 +83,23 @@ int critiprefill_estimate(const critiprefill_params *p, const void *q, const voi
                           void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * critiprefill_estimate for callers that cannot allocate device memory and have no workspace to hand in
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels and
+ * the same result, bit for bit, with the scratch in a fixed array inside the library's device image
+ * instead of a caller workspace.  Calls no allocating routine.
+ * Limit: critiprefill_workspace_bytes(p) must not exceed CRITIPREFILL_STATIC_SCRATCH_BYTES (32 MiB; the five
+ * benchmark configurations need 1 to 28 MiB), otherwise CP_ERR_WORKSPACE and nothing is launched.
+ * Every GPU the library runs on holds its own copy of the array until the process ends; the device that is
+ * current at the call is used (it must be the device of hip_stream).  All calls on one GPU share the array:
+ * two calls whose kernels may overlap (different streams, or threads) race; calls on one stream are ordered.
+ * Nothing in the array has to start at zero (every value read by a call was written by that call).
+ * CP_ERR_LAUNCH if the array's device address cannot be resolved.
+ */
+#define CRITIPREFILL_STATIC_SCRATCH_BYTES (32u << 20)
+int critiprefill_estimate_static(const critiprefill_params *p, const void *q, const void *k,
+                                 const float *prev_scores, float *scores, void *hip_stream);
+
+/*
  * Algorithm 2, the top-k line.  For every row (batch, head, segment j) of scores: the candidates are
  * blocks 0 .. j*r - L_j - 1 with L_j = min(local_blocks, j*r); the min(budget_blocks, #candidates)
  * largest scores are kept (ties to the smaller index); the list written to

@@ -16,7 +16,7 @@ _lib = None
 
 CP_DTYPE_FP32, CP_DTYPE_BF16 = 0, 1
 EXPORTS = ["critiprefill_list_len", "critiprefill_workspace_bytes", "critiprefill_estimate",
-           "critiprefill_select", "critiprefill_sparse_attn", "critiprefill_select_shared",
+           "critiprefill_estimate_static", "critiprefill_select", "critiprefill_sparse_attn", "critiprefill_select_shared",
            "critiprefill_sparse_attn_shared", "critiprefill_dense_causal_attn",
            "critiprefill_strerror", "critiprefill_version"]
 
@@ -53,6 +53,7 @@ def load():
     lib.critiprefill_list_len.argtypes = [P]; lib.critiprefill_list_len.restype = ctypes.c_int32
     lib.critiprefill_workspace_bytes.argtypes = [P]; lib.critiprefill_workspace_bytes.restype = sz
     lib.critiprefill_estimate.argtypes = [P, vp, vp, vp, vp, vp, sz, vp]; lib.critiprefill_estimate.restype = ctypes.c_int
+    lib.critiprefill_estimate_static.argtypes = [P, vp, vp, vp, vp, vp]; lib.critiprefill_estimate_static.restype = ctypes.c_int
     lib.critiprefill_select.argtypes = [P, vp, vp, vp, vp]; lib.critiprefill_select.restype = ctypes.c_int
     lib.critiprefill_sparse_attn.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp]; lib.critiprefill_sparse_attn.restype = ctypes.c_int
     lib.critiprefill_select_shared.argtypes = [P, vp, vp, vp, vp]; lib.critiprefill_select_shared.restype = ctypes.c_int
@@ -123,6 +124,11 @@ def critiprefill_estimate(p, q, k, prev_scores, scores, workspace, stream=None):
     _check(load().critiprefill_estimate(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(prev_scores), _ptr(scores),
                                         _ptr(workspace), workspace.numel() * workspace.element_size(),
                                         _stream(stream)), "critiprefill_estimate")
+
+
+def critiprefill_estimate_static(p, q, k, prev_scores, scores, stream=None):
+    _check(load().critiprefill_estimate_static(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(prev_scores), _ptr(scores),
+                                               _stream(stream)), "critiprefill_estimate_static")
 
 
 def critiprefill_select(p, scores, block_idx, block_cnt, stream=None):

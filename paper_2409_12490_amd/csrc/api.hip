@@ -3,8 +3,31 @@
 #include "kernels.h"
 
 #include <cmath>
+#include <mutex>
+
+// Scratch of critiprefill_estimate_static: the representatives and score statistics that critiprefill_estimate
+// keeps in the caller's workspace.  One copy per GPU the library runs on, held until the process ends.  In host
+// code this name is only a handle for hipGetSymbolAddress; kernels and copies get the resolved device address.
+static __device__ __align__(256) unsigned char scratch[CRITIPREFILL_STATIC_SCRATCH_BYTES];
 
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];    // device address of `scratch` on each device, resolved on first use
+
+// Device address of this device's copy of `scratch` (nullptr on failure).
+void* static_scratch() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
 
 constexpr int kMaxBlocks = 8192;     // score kernel keeps four logit rows in LDS; select keeps a row in registers
 
@@ -92,21 +115,30 @@ size_t critiprefill_workspace_bytes(const critiprefill_params* p) {
     return workspace_layout(sh, nullptr, nullptr);
 }
 
-int critiprefill_estimate(const critiprefill_params* p, const void* q, const void* k, const float* prev_scores,
-                          float* scores, void* workspace, size_t workspace_bytes, void* hip_stream) {
+namespace {
+// use_static: the workspace is this device's static scratch (limited to CRITIPREFILL_STATIC_SCRATCH_BYTES)
+int estimate_common(const critiprefill_params* p, const void* q, const void* k, const float* prev_scores,
+                    float* scores, void* workspace, size_t workspace_bytes, bool use_static, void* hip_stream) {
     cp::Shape sh;
     int e = make_shape(p, &sh);
     if (e != CP_OK) return e;
-    if (!q || !k || !scores || !workspace) return CP_ERR_NULL;
+    if (!q || !k || !scores || (!use_static && !workspace)) return CP_ERR_NULL;
     if (sh.n2 > kMaxBlocks) return CP_ERR_UNSUPPORTED;
     if (sh.dtype == CP_DTYPE_BF16 && (long long)sh.batch * sh.hq > 65535) return CP_ERR_UNSUPPORTED;   // grid.z of the score kernels
-    if (!aligned16(q) || !aligned16(k) || !aligned16(scores) || !aligned16(workspace) ||
+    if (!aligned16(q) || !aligned16(k) || !aligned16(scores) || (!use_static && !aligned16(workspace)) ||
         (prev_scores && !aligned16(prev_scores)))
         return CP_ERR_ALIGN;
     if ((e = check_strides(sh.qs, cp::kHeadDim)) != CP_OK) return e;
     if ((e = check_strides(sh.kvs, cp::kHeadDim)) != CP_OK) return e;
     size_t koff = 0, soff = 0;
-    if (workspace_bytes < workspace_layout(sh, &koff, &soff)) return CP_ERR_WORKSPACE;
+    const size_t need = workspace_layout(sh, &koff, &soff);
+    if (use_static) {
+        if (need > (size_t)CRITIPREFILL_STATIC_SCRATCH_BYTES) return CP_ERR_WORKSPACE;
+        workspace = static_scratch();
+        if (!workspace) return CP_ERR_LAUNCH;
+    } else if (workspace_bytes < need) {
+        return CP_ERR_WORKSPACE;
+    }
     hipStream_t st = (hipStream_t)hip_stream;
     void* qrep = workspace;
     void* krep = (char*)workspace + koff;
@@ -114,6 +146,17 @@ int critiprefill_estimate(const critiprefill_params* p, const void* q, const voi
     float* stats = (float*)((char*)workspace + soff);
     if (cp::launch_score(sh, qrep, krep, prev_scores, scores, stats, st) != hipSuccess) return CP_ERR_LAUNCH;
     return CP_OK;
+}
+}  // namespace
+
+int critiprefill_estimate(const critiprefill_params* p, const void* q, const void* k, const float* prev_scores,
+                          float* scores, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return estimate_common(p, q, k, prev_scores, scores, workspace, workspace_bytes, false, hip_stream);
+}
+
+int critiprefill_estimate_static(const critiprefill_params* p, const void* q, const void* k,
+                                 const float* prev_scores, float* scores, void* hip_stream) {
+    return estimate_common(p, q, k, prev_scores, scores, nullptr, 0, true, hip_stream);
 }
 
 namespace {
@@ -195,6 +238,6 @@ const char* critiprefill_strerror(int status) {
     }
 }
 
-int critiprefill_version(void) { return 100; }
+int critiprefill_version(void) { return 200; }
 
 }  // extern "C"

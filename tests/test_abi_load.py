@@ -26,7 +26,7 @@ def test_header_functions_are_exported():
     assert set(names) == set(B.EXPORTS)
     for name in names:
         assert getattr(lib, name) is not None
-    assert B.version() >= 100
+    assert B.version() >= 200
     assert B.strerror(0) == "ok"
 
 
@@ -65,6 +65,7 @@ def test_bad_shapes_are_rejected_before_launch(kw, code):
     p = _params(**kw)
     fake = ctypes.c_void_p(0x1000)        # never dereferenced: the shape check fails first
     assert lib.critiprefill_estimate(ctypes.byref(p), fake, fake, None, fake, fake, 1 << 30, None) == code
+    assert lib.critiprefill_estimate_static(ctypes.byref(p), fake, fake, None, fake, None) == code
     assert lib.critiprefill_select(ctypes.byref(p), fake, fake, fake, None) == code
     assert lib.critiprefill_sparse_attn(ctypes.byref(p), fake, fake, fake, fake, fake, fake, None, None) == code
     assert lib.critiprefill_dense_causal_attn(ctypes.byref(p), fake, fake, fake, fake, None, None) == code
@@ -89,6 +90,11 @@ def test_null_alignment_and_workspace_errors():
     assert lib.critiprefill_estimate(ctypes.byref(p), None, ok, None, ok, ok, 1 << 30, None) == -1
     assert lib.critiprefill_estimate(ctypes.byref(p), odd, ok, None, ok, ok, 1 << 30, None) == -4
     assert lib.critiprefill_estimate(ctypes.byref(p), ok, ok, None, ok, ok, 16, None) == -5
+    assert lib.critiprefill_estimate_static(ctypes.byref(p), ok, None, None, ok, None) == -1
+    assert lib.critiprefill_estimate_static(ctypes.byref(p), ok, ok, odd, ok, None) == -4
+    big = _params(n_q_heads=64, n_kv_heads=64, seq_len=131072, segment_size=512, block_size=16)   # needs > 32 MiB of scratch
+    assert B.critiprefill_workspace_bytes(big) > (32 << 20)
+    assert lib.critiprefill_estimate_static(ctypes.byref(big), ok, ok, None, ok, None) == -5
     assert lib.critiprefill_select(ctypes.byref(p), ok, None, ok, None) == -1
     assert lib.critiprefill_select(ctypes.byref(p), ok, odd, ok, None) == -4
     assert lib.critiprefill_sparse_attn(ctypes.byref(p), ok, ok, ok, None, ok, ok, None, None) == -1
