@@ -76,10 +76,12 @@ __device__ __forceinline__ void pin(const bf16x8& v) { asm volatile("" ::"v"(v))
 // 16 bytes per lane from global memory (uniform base + per-lane byte offset) straight into LDS at
 // (lds_base + lane * 16); lds_base is wave-uniform.  Issued through inline asm so the compiler does not
 // serialise later LDS reads of OTHER ring slots behind it; the matching s_waitcnt vmcnt is placed by hand
-// before the tile barrier.
+// before the tile barrier.  m0 is written here and not named as a clobber: it is a reserved register for the
+// compiler, which keeps no value in it across statements and sets it anew before each use of its own (naming it
+// only draws "clobber list contains reserved registers").
 __device__ __forceinline__ void dma16(const void* sbase, unsigned voff, unsigned lds_base) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase)
-                 : "memory", "m0");
+                 : "memory");
 }
 
 __device__ __forceinline__ const uint16_t* uniform_ptr(const uint16_t* p) {   // into SGPRs

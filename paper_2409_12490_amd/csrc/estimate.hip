@@ -352,7 +352,7 @@ __device__ __forceinline__ void score_load_piece(const ScoreArgs& a, const Score
         const unsigned dst =
             __builtin_amdgcn_readfirstlane(c.lds0 + (p & 1) * kPieceBytes + 1024u * (kPerWave * c.wave + x));
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(voff), "s"(sbase)
-                     : "memory", "m0");
+                     : "memory");   // m0: reserved for the compiler, which sets it anew before each use of its own
     }
 }
 // every load of this wave has landed, every wave has arrived (and is done with the buffer that is filled next)
