@@ -39,6 +39,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 v4bf16_lds;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(2))) int i32x2;
 #define LDS_PTR(T, off) ((__attribute__((address_space(3))) T*)(uintptr_t)(off))
 
 constexpr int TQ = 256;               // query rows per workgroup
@@ -101,10 +102,12 @@ __device__ __forceinline__ float half_sum(float x) {
 }
 
 // MODE 0: sparse, any block size (row tokens of every tile kept in LDS); MODE 1: sparse, block size a
-// multiple of 64 (every tile is 64 consecutive tokens, described by its first token alone); MODE 2: dense.
+// multiple of 64 (every tile is 64 consecutive tokens, described by its first token alone); MODE 2: dense;
+// MODE 3: sparse, block size a multiple of 32 but not of 64 (the paper's own setting is 32): a tile is two runs
+// of 32 consecutive tokens, described by their two first tokens.
 template <int MODE>
 __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
-    constexpr bool DENSE = MODE == 2, FAST = MODE != 0;
+    constexpr bool DENSE = MODE == 2, FAST = MODE != 0, HALF = MODE == 3;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
@@ -174,11 +177,28 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
     const unsigned total = DENSE ? (unsigned)q_last + 1u : (unsigned)count * (unsigned)a.b;
     const unsigned ub = (unsigned)a.b;
     int ntiles = (int)((total + TK - 1) / TK);
+    // MODE 3: the first tokens of the two halves of every tile, worked out once by all threads and kept in LDS
+    // behind the list (8 bytes per tile), so that the key loop reads a tile's description instead of walking the list
+    const unsigned tab0 = lds0 + kListOff + (((unsigned)a.list_len * 4u + 1023u) & ~1023u);
+    if (HALF) {
+        for (int x = tid; x < ntiles; x += 512) {
+            const unsigned p0 = (unsigned)x * TK, e0 = p0 / ub, p1 = p0 + 32, e1 = p1 / ub;
+            const int lo = *LDS_PTR(const int, lds0 + kListOff + e0 * 4) * a.b + (int)(p0 - e0 * ub);
+            const int hi = e1 < (unsigned)count ? *LDS_PTR(const int, lds0 + kListOff + e1 * 4) * a.b + (int)(p1 - e1 * ub) : -1;
+            i32x2 d; d[0] = lo; d[1] = hi;
+            *LDS_PTR(i32x2, tab0 + x * 8) = d;
+        }
+        __syncthreads();
+    }
     if (!DENSE) {   // drop trailing tiles that start after the last query row (lists are ascending)
         while (ntiles > 0) {
-            const unsigned p = (unsigned)(ntiles - 1) * TK;
-            const unsigned e = p / ub;
-            const int tok = *LDS_PTR(const int, lds0 + kListOff + e * 4) * a.b + (int)(p - e * ub);
+            int tok;
+            if (HALF) tok = *LDS_PTR(const int, tab0 + (ntiles - 1) * 8);
+            else {
+                const unsigned p = (unsigned)(ntiles - 1) * TK;
+                const unsigned e = p / ub;
+                tok = *LDS_PTR(const int, lds0 + kListOff + e * 4) * a.b + (int)(p - e * ub);
+            }
             if (tok <= q_last) break;
             --ntiles;
         }
@@ -214,6 +234,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
     int ent[2], eoff[2], tokv[2];
     // MODE 1/2 state: first token of tiles t .. t+3 (-1: no such tile) and the walk over the list.
     int nb[4] = {-1, -1, -1, -1};
+    int nb2[4] = {-1, -1, -1, -1};                           // MODE 3: first token of the second half of tiles t .. t+3
     int walk_e = 0, walk_off = 0, dense_tile = 0;
     unsigned lane_k[2], lane_v[2];
 #pragma unroll
@@ -252,7 +273,12 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
         }
     };
     int pre_ent = 0; bool early = false;                   // the list entry of the next walk step, fetched at the start of the tile step
-    auto prefetch_entry = [&]() { if (FAST && !DENSE) { pre_ent = *LDS_PTR(const int, lds0 + kListOff + min(walk_e, max(count - 1, 0)) * 4); early = true; } };
+    i32x2 pre_tile = {-1, -1};                     // MODE 3: the description of the next tile to queue
+    int walk_t = 0;                                        // MODE 3: that tile's index
+    auto prefetch_entry = [&]() {
+        if (HALF) { pre_tile = *LDS_PTR(const i32x2, tab0 + min(walk_t, max(ntiles - 1, 0)) * 8); early = true; }
+        else if (FAST && !DENSE) { pre_ent = *LDS_PTR(const int, lds0 + kListOff + min(walk_e, max(count - 1, 0)) * 4); early = true; }
+    };
     auto next_base = [&]() -> int {                          // MODE 1/2: first token of the next tile in order, -1 past the end
         int base = -1;
         if (DENSE) {
@@ -265,6 +291,30 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
             if (walk_off >= a.b) { walk_off = 0; ++walk_e; }
         }
         return base;
+    };
+    auto next_halves = [&](int& lo, int& hi) {               // MODE 3: the next tile in order, (-1, -1) past the end
+        i32x2 d = pre_tile;
+        if (!early) d = *LDS_PTR(const i32x2, tab0 + min(walk_t, max(ntiles - 1, 0)) * 8);
+        const bool ok = walk_t < ntiles;
+        lo = ok ? __builtin_amdgcn_readfirstlane(d[0]) : -1;
+        hi = ok ? __builtin_amdgcn_readfirstlane(d[1]) : -1;
+        ++walk_t;
+    };
+    auto half_offsets = [&](int lo, int hi) {                // MODE 3: offsets of the tile whose halves start at lo / hi
+        if (lo >= 0 && hi >= 0 && lo <= a.n - 32 && hi <= a.n - 32) {   // uniform: both halves exist in full
+            const unsigned s0 = (unsigned)lo * tok_bytes, s1 = (unsigned)(hi - 32) * tok_bytes;   // lane_k[1] holds row 32 + ...
+            koff[0] = s0 + lane_k[0]; voff[0] = s0 + lane_v[0];
+            koff[1] = s1 + lane_k[1]; voff[1] = s1 + lane_v[1];
+        } else {                                             // ragged or missing half: rows without a token read token 0
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int base = i ? hi : lo;
+                const int tok = base + 4 * wave + r4;
+                const bool valid = base >= 0 && (unsigned)tok < (unsigned)a.n;
+                const unsigned sb = __umul24(valid ? (unsigned)tok : 0u, tok_bytes);
+                koff[i] = sb + kch * 16; voff[i] = sb + vch * 16;
+            }
+        }
     };
     auto base_offsets = [&](int base) {                      // MODE 1/2: offsets of the tile that starts at token base
         if (base >= 0 && base <= a.n - TK) {                 // uniform: the whole tile exists
@@ -286,7 +336,12 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
     // describe the next tile in order (its DMA offsets go to koff/voff); MODE 0 also publishes its row tokens
     auto describe_next = [&](int slot) {
         voff_issue[0] = voff[0]; voff_issue[1] = voff[1];
-        if (FAST) {
+        if (HALF) {
+            nb[0] = nb[1]; nb[1] = nb[2]; nb[2] = nb[3];
+            nb2[0] = nb2[1]; nb2[1] = nb2[2]; nb2[2] = nb2[3];
+            next_halves(nb[3], nb2[3]);
+            half_offsets(nb[3], nb2[3]);
+        } else if (FAST) {
             nb[0] = nb[1]; nb[1] = nb[2]; nb[2] = nb[3]; nb[3] = next_base();
             base_offsets(nb[3]);
         } else {
@@ -430,6 +485,20 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
                 for (int i = 0; i < 4; ++i)
                     if (32 * kt + 8 * gg + i > lim) s[kt][4 * gg + i] = -INFINITY;
     };
+    // MODE 3: key row 32*kt + kr of the tile is token (kt ? hi : lo) + kr; a missing half (-1) is masked whole
+    auto mask_halves = [&](f32x16 (&s)[2], int lo, int hi) {
+        const int top = min(qpos, a.n - 1) - 4 * hh;
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt) {
+            const int base = kt ? hi : lo;
+            const int lim = base < 0 ? -1 : top - base;
+#pragma unroll
+            for (int gg = 0; gg < 4; ++gg)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (8 * gg + i > lim) s[kt][4 * gg + i] = -INFINITY;
+        }
+    };
     // S^T tile -> P^T fragments; running max / sum; O rescaled when any row's max moved
     auto sm = [&](f32x16 (&s)[2], bf16x8 (&pf)[4]) {
         float mx = fmaxf(s[0][0], s[0][1]), my = fmaxf(s[1][0], s[1][1]);   // two chains of v_max3
@@ -481,7 +550,11 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
         return FAST ? (base >= 0 && base <= wq_last) : (first_tok(slot) <= wq_last);
     };
     auto mask_if_needed = [&](f32x16 (&s)[2], int slot, int base) {
-        if (FAST) { if (base + TK - 1 > wq_lo || base + TK > a.n) mask_base(s, base); }
+        if (HALF) {                                          // slot: position in the nb / nb2 queue (0 = this tile)
+            const int hi = nb2[0], top = max(base, hi);
+            if (hi < 0 || top + 31 > wq_lo || top + 32 > a.n) mask_halves(s, base, hi);
+        }
+        else if (FAST) { if (base + TK - 1 > wq_lo || base + TK > a.n) mask_base(s, base); }
         else { if (last_tok(slot) > wq_lo) mask(s, slot); }
     };
     // end of a tile step: tile t+2 has landed (this wave's rows; at most the 4 loads of tile t+3 are still in
@@ -499,7 +572,8 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
         if (!FAST) fetch_entries();
 #pragma unroll
         for (int s3 = 0; s3 < 4; ++s3) {
-            if (FAST) { nb[s3] = next_base(); base_offsets(nb[s3]); }
+            if (HALF) { next_halves(nb[s3], nb2[s3]); half_offsets(nb[s3], nb2[s3]); }
+            else if (FAST) { nb[s3] = next_base(); base_offsets(nb[s3]); }
             else { tile_offsets(); fetch_entries(); put_tok(s3); }
             if (s3 == 0) { issue_k(0); issue_v(0, true); }
             if (s3 == 1) { issue_k(1); }                     // K0 V0 K1 first: they are needed at once
@@ -620,10 +694,15 @@ hipError_t launch_attn_bf16(const Shape& sh, const void* q, const void* k, const
         a.qtiles = (sh.s + TQ - 1) / TQ;
         const long long grid = (long long)sh.batch * sh.hq * sh.n1 * a.qtiles;
         const int smem = kListOff + ((sh.list_len * 4 + 1023) & ~1023);
+        const int tab_bytes = (int)(((long long)sh.list_len * sh.b + TK - 1) / TK) * 8;     // MODE 3: tile descriptions
         if (sh.b % TK == 0) {
             e = hipFuncSetAttribute((const void*)attn_bf16_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL(attn_bf16_kernel<1>, dim3((unsigned)grid), dim3(512), smem, st, a);
+        } else if (sh.b % 32 == 0 && smem + tab_bytes <= 160 * 1024) {
+            e = hipFuncSetAttribute((const void*)attn_bf16_kernel<3>, hipFuncAttributeMaxDynamicSharedMemorySize, smem + tab_bytes);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL(attn_bf16_kernel<3>, dim3((unsigned)grid), dim3(512), smem + tab_bytes, st, a);
         } else {
             e = hipFuncSetAttribute((const void*)attn_bf16_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
             if (e != hipSuccess) return e;
