@@ -169,8 +169,9 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
     if (!DENSE) {
         const long long lrow = a.shared_lists ? ((long long)bb * a.hkv + g) * a.n1 + j : ((long long)bb * a.hq + h) * a.n1 + j;
         const int32_t* list = a.idx + lrow * a.list_len;
+        // the whole row (its pitch is list_len) is copied, so that its loads do not wait for the count
+        for (int x = tid; x < a.list_len; x += 512) *LDS_PTR(int, lds0 + kListOff + x * 4) = list[x];
         count = min(max(a.cnt[lrow], 0), a.list_len);             // a bad count must not run past the list's LDS region
-        for (int x = tid; x < count; x += 512) *LDS_PTR(int, lds0 + kListOff + x * 4) = list[x];
     }
     __syncthreads();
     // positions 0 .. total-1 of the listed blocks laid end to end (host checks count * b < 2^31)
@@ -223,8 +224,12 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
         for (int i = 0; i < 2; ++i)
             dma16(vp, first ? voff[i] : voff_issue[i], lds0 + kVOff + slot * kTileBytes + (32 * i + 4 * wave) * 256);
     };
-    auto dma_wait = [&]() {                                  // all but the 4 loads of the newest tile pair have landed
-        asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    // all loads but those issued in this step have landed (the last steps of a workgroup issue two or none: there
+    // is no tile left to fetch)
+    auto dma_wait = [&](int issued) {
+        if (issued == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else if (issued == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     };
 
     // MODE 0 state: the list is walked incrementally per lane row: (e, off) = (entry, offset inside the
@@ -560,9 +565,9 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
     // end of a tile step: tile t+2 has landed (this wave's rows; at most the 4 loads of tile t+3 are still in
     // flight), then everybody is past its reads of tile t; afterwards the loader moves on to tile t+4 (its
     // row tokens, in MODE 0, go into the slot tile t just vacated).
-    auto step_end = [&](int slot) {
+    auto step_end = [&](int slot, int issued) {
         if (FAST) describe_next(slot);                       // registers only
-        dma_wait();
+        dma_wait(issued);
         __syncthreads();
         if (!FAST) describe_next(slot);                      // writes the row tokens into the vacated slot
     };
@@ -585,7 +590,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
     }
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) pin(qf[ks]);                      // Q has arrived: no wait for it is left in the key loop
-    if (ntiles > 0) dma_wait();                                      // K0, V0, K1 have landed
+    if (ntiles > 0) dma_wait(4);                                     // K0, V0, K1 have landed
     __syncthreads();
     // from here on: koff = K offsets of tile 3, voff_issue = V offsets of tile 2, voff = V offsets of tile 3
 
@@ -606,8 +611,9 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
             else if (act) qk(s);
             else if (have_p) pv(pf);
             __builtin_amdgcn_s_setprio(0);
-            issue_v((t + 2) & 3, false);                                 // after the matrix phase, which starts with the step
-            issue_k((t + 3) & 3);
+            const int issued = t + 3 < ntiles ? 4 : (t + 2 < ntiles ? 2 : 0);
+            if (issued >= 2) issue_v((t + 2) & 3, false);                // after the matrix phase, which starts with the step
+            if (issued == 4) issue_k((t + 3) & 3);
             next_k_slot(); next_v_slot();                                // K(t+1), V(t)
             const bool act_next = act && (t + 1 < ntiles) && tile_active(nslot, nb[1]);
             if (act) {
@@ -616,7 +622,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
                 sm(s, pf);
             }
             have_p = act; act = act_next;
-            step_end(slot);
+            step_end(slot, issued);
         }
         if (have_p) pv(pf);
     } else {
@@ -637,11 +643,12 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
                 else pv(pf);
                 __builtin_amdgcn_s_setprio(0);
             }
-            issue_v((t + 2) & 3, false);                                 // after the matrix phase, like waves 0-3
-            issue_k((t + 3) & 3);
+            const int issued = t + 3 < ntiles ? 4 : (t + 2 < ntiles ? 2 : 0);
+            if (issued >= 2) issue_v((t + 2) & 3, false);                // after the matrix phase, like waves 0-3
+            if (issued == 4) issue_k((t + 3) & 3);
             next_k_slot(); next_v_slot();
             have_s = act_next;
-            step_end(slot);
+            step_end(slot, issued);
         }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                 // no DMA may outlive the workgroup
