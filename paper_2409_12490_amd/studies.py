@@ -17,15 +17,18 @@
     16K tokens: (i) overlap |K_i ∩ K_j| / k of the exact per-query top-k token sets of queries i and j = i + delta, for
     delta = 1 .. 4096; (ii) how much of a query's exact top-k set, and of its softmax mass, the block lists of the
     library (estimate + select) retain, against lists of the same size made of the most recent blocks only.  A
-    quality proxy that needs no dataset and no trained weights.  The exact per-query sets are the reference here and
-    come from plain torch operations on the GPU (a dense score matrix and ``topk``); the block lists come from the
-    library.
+    quality proxy that needs no dataset and no trained weights.  A query's exact set is the top-k of q.k among the
+    strictly earlier keys plus its own position (the convention of the path: the diagonal is always attended); the
+    sets come from plain torch operations on the GPU (a dense score matrix and ``topk``) and are checked against the
+    CPU checker's own per-query top-k (segment = block = 1) in tests/test_gpu_studies.py; the block lists come from
+    the library.
 
 ``python -m paper_2409_12490_amd.studies shared``
     One block list per KV head (from the maximum of its query heads' scores) instead of one per query head, an
     extension the paper does not describe: latency of select + sparse attention and the change of the output error
     (against the library's dense kernel) at 128K, for the budget of the benchmark and for a budget G times larger
-    (the union of G per-head lists is at most that long).
+    (the union of G per-head lists is at most that long); on the Llama3-8B shape (4 query heads per KV head) and the
+    Yi-9B shape (8 per KV head), the latter also with blocks of 32 tokens.
 
 Inputs are the seeded synthetic Q/K/V of ``synth``; every latency and every block list comes from the HIP library
 through the C ABI.
@@ -104,7 +107,32 @@ def length(dev: str = "cuda:0") -> None:
         del q, k, v, out
 
 
-def locality(dev: str = "cuda:0", seq_len: int = 16384, heads=(0, 5, 10, 15, 20, 25, 30, 31), topk: int = 1024) -> None:
+def exact_topk_members(qh: torch.Tensor, kh: torch.Tensor, topk: int, scale: float):
+    """The exact critical set of every query of one head (Eq. 3 of the paper, with the convention the path itself
+    uses): the ``topk`` keys with the largest q.k among the strictly earlier positions, plus the query's own
+    position.  qh, kh: [n, d] float32 on the GPU.  Returns (member [n, n] bool, prob [n, n] float32 = the causal
+    softmax of the scaled logits)."""
+    n, dev = qh.shape[0], qh.device
+    rows = torch.arange(n, device=dev)
+    member = torch.zeros((n, n), dtype=torch.bool, device=dev)
+    prob_rows = []
+    kk = min(topk, n)
+    for r0 in range(0, n, 2048):
+        z = (qh[r0:r0 + 2048] @ kh.T) * scale
+        zc = z.masked_fill(rows[None, :] > rows[r0:r0 + 2048, None], float("-inf"))
+        prob_rows.append(torch.softmax(zc, dim=1))
+        zs = z.masked_fill(rows[None, :] >= rows[r0:r0 + 2048, None], float("-inf"))
+        top = zs.topk(kk, dim=1).indices
+        member[r0:r0 + 2048].scatter_(1, top, True)
+    member &= rows[None, :] < rows[:, None]                  # queries with fewer than topk earlier keys: drop the padding picks
+    member |= rows[None, :] == rows[:, None]
+    return member, torch.cat(prob_rows)
+
+
+def locality(dev: str = "cuda:0", seq_len: int = 16384, heads=(0, 5, 10, 15, 20, 25, 30, 31), topk: int = 1024,
+             keep_sets: dict | None = None) -> None:
+    """keep_sets: optional dict that receives, per (setting label, head), the exact sets (bool [n, n], on the CPU)
+    and the library's block lists, for checks against an independent implementation."""
     w = synth.WORKLOADS["c2_llama3_8b_16k"].replace(seq_len=seq_len, name=f"llama3_8b_{seq_len // 1024}k")
     q, k, _ = synth.make_qkv(w, threads=min(16, os.cpu_count() or 8))
     q, k = q.to(dev), k.to(dev)
@@ -124,38 +152,33 @@ def locality(dev: str = "cuda:0", seq_len: int = 16384, heads=(0, 5, 10, 15, 20,
         overlap = {d: [] for d in deltas}
         kept_set, kept_mass, recent_set, recent_mass = [], [], [], []
         for h in heads:
-            qh, kh = q[0, h].float(), k[0, h // G].float()
-            # exact sets: top-k visible tokens of every query with at least topk visible tokens
-            member = torch.zeros((n, n), dtype=torch.bool, device=dev)
-            prob_rows = []
-            for r0 in range(0, n, 2048):
-                z = (qh[r0:r0 + 2048] @ kh.T) * scale
-                z.masked_fill_(rows[None, :] > rows[r0:r0 + 2048, None], float("-inf"))
-                top = z.topk(topk, dim=1).indices
-                member[r0:r0 + 2048].scatter_(1, top, True)
-                prob_rows.append(torch.softmax(z, dim=1))
-            member &= rows[None, :] <= rows[:, None]          # rows with fewer than topk visible tokens: drop the padding picks
-            full = rows >= topk                               # queries whose set has exactly topk members
+            member, prob = exact_topk_members(q[0, h].float(), k[0, h // G].float(), topk, scale)
+            size = member.sum(1).float()                      # topk + 1 once a query has topk earlier keys
+            full = rows >= topk
             for d in deltas:
-                both = (member[:-d] & member[d:]).sum(1).float() / topk
+                both = (member[:-d] & member[d:]).sum(1).float() / size[d:]
                 overlap[d].append(float(both[full[:-d]].mean()))
             # what the block lists keep: tokens of the listed blocks, per segment; and the same number of most recent blocks
             tok_block = rows // b
-            listed = torch.zeros((n1, n2), dtype=torch.bool, device=dev)
             li = idx[0, h].long(); lc = cnt[0, h].long()
             valid = torch.arange(li.shape[1], device=dev)[None, :] < lc[:, None]
-            listed.scatter_(1, li.clamp(min=0), valid)
+            # (added up, not assigned: the padding entries are clamped onto block 0 and must not unmark it)
+            listed = torch.zeros((n1, n2), dtype=torch.int32, device=dev).scatter_add_(1, li.clamp(min=0), valid.int()) > 0
             seg = rows // s
             recent = torch.zeros((n1, n2), dtype=torch.bool, device=dev)
             blocks = torch.arange(n2, device=dev)
             last = (torch.arange(n1, device=dev) + 1) * r           # first block after the segment
             recent |= (blocks[None, :] < last[:, None]) & (blocks[None, :] >= (last - lc)[:, None])
-            prob = torch.cat(prob_rows)
             for mask_blocks, out_set, out_mass in ((listed, kept_set, kept_mass), (recent, recent_set, recent_mass)):
                 tok_mask = mask_blocks[seg][:, tok_block]           # [query, token]: the token's block is in the query's list
-                out_set.append(float(((member & tok_mask).sum(1).float() / topk)[full].mean()))
+                out_set.append(float(((member & tok_mask).sum(1).float() / size)[full].mean()))
                 out_mass.append(float((prob * tok_mask).sum(1)[full].mean()))
-            del member, prob, prob_rows
+            if keep_sets is not None:
+                keep_sets[(label, h)] = {"member": member.cpu(), "idx": idx[0, h].cpu(), "cnt": cnt[0, h].cpu(),
+                                         "block": b, "segment": s, "budget_blocks": budget_blocks, "local_blocks": local,
+                                         "kept_of_set": kept_set[-1], "recent_of_set": recent_set[-1],
+                                         "overlap": {d: overlap[d][-1] for d in deltas}}
+            del member, prob
         mean = lambda xs: round(sum(xs) / len(xs), 4)
         print(json.dumps({"study": "locality", "seq_len": n, "setting": label, "heads": list(heads), "topk_tokens": topk,
                           "overlap_of_exact_topk_sets_by_query_distance": {str(d): mean(v) for d, v in overlap.items()},
@@ -166,8 +189,11 @@ def locality(dev: str = "cuda:0", seq_len: int = 16384, heads=(0, 5, 10, 15, 20,
                           "blocks_total": n2}), flush=True)
 
 
-def shared(dev: str = "cuda:0") -> None:
-    w = synth.WORKLOADS["c3_llama3_8b_128k"]
+def shared(dev: str = "cuda:0", workload: str = "c3_llama3_8b_128k", block_size: int = 0) -> None:
+    w = synth.WORKLOADS[workload]
+    if block_size:                                          # same token budget and local window in blocks of another size
+        f = w.block_size // block_size
+        w = w.replace(block_size=block_size, budget_blocks=w.budget_blocks * f, local_blocks=w.local_blocks * f)
     q, k, v = synth.make_qkv(w, threads=min(16, os.cpu_count() or 8))
     q, k, v = q.to(dev), k.to(dev), v.to(dev)
     out, dense = torch.empty_like(q), torch.empty_like(q)
@@ -194,7 +220,7 @@ def shared(dev: str = "cuda:0") -> None:
                 att = lambda: B.critiprefill_sparse_attn_shared(p, q, k, v, idx, cnt, out, None)
             sel(); att(); torch.cuda.synchronize()
             e_max, e_rel = err(out)
-            print(json.dumps({"study": "shared", "workload": w.name, "lists": kind, "budget_blocks": budget,
+            print(json.dumps({"study": "shared", "workload": w.name, "block_size": w.block_size, "group": G, "lists": kind, "budget_blocks": budget,
                               "select_ms": round(_time(sel, 10), 4), "sparse_attn_ms": round(_time(att, 10), 4),
                               "max_abs_vs_dense": round(e_max, 4), "rel_l2_vs_dense": round(e_rel, 5),
                               "mean_listed_blocks": round(float(cnt.float().mean()), 2)}), flush=True)
@@ -209,7 +235,12 @@ def main(argv) -> int:
         return 2
     B.load()
     torch.cuda.set_device(0)
-    {"fusion": fusion, "length": length, "locality": locality, "shared": shared}[argv[1]]()
+    if argv[1] == "shared":
+        # group 4 and 8, block 64 and 32: is the gather of K/V tiles per query head (instead of once per KV head) a cost?
+        for workload, block in (("c3_llama3_8b_128k", 0), ("c4_yi_9b_128k", 0), ("c4_yi_9b_128k", 32)):
+            shared(workload=workload, block_size=block)
+        return 0
+    {"fusion": fusion, "length": length, "locality": locality}[argv[1]]()
     return 0
 
 
