@@ -105,7 +105,8 @@ __device__ __forceinline__ float half_sum(float x) {
 // multiple of 64 (every tile is 64 consecutive tokens, described by its first token alone); MODE 2: dense;
 // MODE 3: sparse, block size a multiple of 32 but not of 64 (the paper's own setting is 32): a tile is two runs
 // of 32 consecutive tokens, described by their two first tokens.
-template <int MODE>
+constexpr int kFragLook = 3;               // depth of the LDS fragment ring, see the matrix phase
+template <int MODE, int KLOOK = kFragLook>
 __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
     constexpr bool DENSE = MODE == 2, FAST = MODE != 0, HALF = MODE == 3;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -377,10 +378,12 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
     const float lazy_raw = kLazyLog2 / c;                        // the same margin in units of the raw logits
 
     // ---- the three phases ---------------------------------------------------------------------
-    // LDS fragments are read in groups of four (4 MFMAs each) into two alternating register groups, one
-    // group ahead of their use, so that an MFMA does not wait a full LDS round trip.  The first group of a
-    // matrix phase is issued before the softmax phase that precedes it.
-    bf16x8 fr[2][4];
+    // LDS fragments reach the MFMAs through a small ring of registers: the read of fragment j + kLook is issued
+    // before the MFMA that consumes fragment j, so every MFMA has its operand kLook MFMAs (32 cycles each) after
+    // the read was issued, with (kLook + 1) x 4 registers in all.  The first kLook fragments of a matrix phase are
+    // read before the softmax phase that precedes it.  (Measured: depth 3 and 4 are equal within 1 %, deeper rings
+    // are slower; reading in groups of four into two alternating register groups costs 12 more registers and is
+    // 0.5 % (sparse) to 2.4 % (dense) slower.)
     // The read addresses carry the ring slot they point into (ka: the K slot, va: the V slot) and are moved on by
     // one slot per tile step, so that a fragment read needs no address arithmetic, only an immediate offset.
     unsigned ka[8], va[4];
@@ -401,34 +404,43 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) va[dt] += d;
     };
-    auto read_kg = [&](int gq, int grp) {                    // K group gq: ks = 2*gq, 2*gq+1, both key halves
-#pragma unroll
-        for (int x = 0; x < 2; ++x)
-#pragma unroll
-            for (int kt = 0; kt < 2; ++kt)
-                fr[grp][2 * x + kt] = as_bf16x8(*LDS_PTR(const u32x4, ka[2 * gq + x] + kt * 32 * 256));
+    constexpr int kLook = KLOOK;
+    bf16x8 ring[kLook + 1];
+    auto read_k = [&](int ks, int kt, bf16x8& f) {           // K: channel step ks, key half kt
+        f = as_bf16x8(*LDS_PTR(const u32x4, ka[ks] + kt * 32 * 256));
     };
-    auto read_vg = [&](int t4, int grp) {                    // V group t4: 16 keys, all four channel tiles
+    auto read_v = [&](int t4, int dt, bf16x8& f) {           // V: 16 keys t4, channel tile dt
+        const unsigned ad = va[dt] + t4 * 16 * 256;
+        const v4bf16_lds lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(v4bf16_lds, ad));
+        const v4bf16_lds hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(v4bf16_lds, ad + 8 * 256));
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt) {
-            const unsigned ad = va[dt] + t4 * 16 * 256;
-            const v4bf16_lds lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(v4bf16_lds, ad));
-            const v4bf16_lds hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(v4bf16_lds, ad + 8 * 256));
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { fr[grp][dt][e] = lo[e]; fr[grp][dt][4 + e] = hi[e]; }
+        for (int e = 0; e < 4; ++e) { f[e] = lo[e]; f[4 + e] = hi[e]; }
+    };
+    // fragment j of a matrix phase.  kind 0: QK alone (16: ks = j / 2, kt = j % 2); kind 1: PV alone (16: t4 = j / 4,
+    // dt = j % 4); kind 2: PV of one tile interleaved with QK of the next in groups of four (32)
+    auto frag_read = [&](int kind, int j, bf16x8& f) __attribute__((always_inline)) {
+        if (kind == 0) read_k(j >> 1, j & 1, f);
+        else if (kind == 1) read_v(j >> 2, j & 3, f);
+        else if ((j & 7) < 4) read_v(j >> 3, j & 3, f);
+        else read_k(2 * (j >> 3) + (((j & 7) - 4) >> 1), j & 1, f);
+    };
+    auto frag_mfma = [&](int kind, int j, const bf16x8& f, f32x16 (&s)[2], const bf16x8 (&pf)[4]) __attribute__((always_inline)) {
+        const bool is_v = kind == 1 || (kind == 2 && (j & 7) < 4);
+        if (is_v) {
+            const int t4 = kind == 1 ? (j >> 2) : (j >> 3), dt = j & 3;
+            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, pf[t4], o[dt], 0, 0, 0);
+        } else {
+            const int ks = kind == 0 ? (j >> 1) : 2 * (j >> 3) + (((j & 7) - 4) >> 1), kt = j & 1;
+            s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, qf[ks], s[kt], 0, 0, 0);
         }
     };
-    auto mfma_kg = [&](int gq, int grp, f32x16 (&s)[2]) {
+    auto read_kg = [&](int, int) __attribute__((always_inline)) {    // first fragments of a phase that starts with QK
 #pragma unroll
-        for (int x = 0; x < 2; ++x)
-#pragma unroll
-            for (int kt = 0; kt < 2; ++kt)
-                s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[grp][2 * x + kt], qf[2 * gq + x], s[kt], 0, 0, 0);
+        for (int j = 0; j < kLook; ++j) frag_read(0, j, ring[j]);
     };
-    auto mfma_vg = [&](int t4, int grp, const bf16x8 (&pf)[4]) {
+    auto read_vg = [&](int, int) __attribute__((always_inline)) {    // ... that starts with PV
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[grp][dt], pf[t4], o[dt], 0, 0, 0);
+        for (int j = 0; j < kLook; ++j) frag_read(1, j, ring[j]);
     };
     auto zero_s = [&](f32x16 (&s)[2]) {
 #pragma unroll
@@ -436,36 +448,21 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
     };
-    auto qk = [&](f32x16 (&s)[2]) {                // S^T = K Q^T; K group 0 already on its way into fr[0]
-        zero_s(s);
+    auto run_frags = [&](int kind, f32x16 (&s)[2], const bf16x8 (&pf)[4]) __attribute__((always_inline)) {
+        const int n = kind == 2 ? 32 : 16;
 #pragma unroll
-        for (int gq = 0; gq < 4; ++gq) {
-            if (gq + 1 < 4) read_kg(gq + 1, (gq + 1) & 1);
-            mfma_kg(gq, gq & 1, s);
-            __builtin_amdgcn_sched_barrier(0);
+        for (int j = 0; j < 32; ++j) {
+            if (j < n) {
+                if (j + kLook < n) frag_read(kind, j + kLook, ring[(j + kLook) % (kLook + 1)]);
+                frag_mfma(kind, j, ring[j % (kLook + 1)], s, pf);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
     };
-    auto pv = [&](const bf16x8 (&pf)[4]) {         // O^T += V^T P^T; V group 0 already on its way into fr[0]
-#pragma unroll
-        for (int t4 = 0; t4 < 4; ++t4) {
-            if (t4 + 1 < 4) read_vg(t4 + 1, (t4 + 1) & 1);
-            mfma_vg(t4, t4 & 1, pf);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
-    // PV of one tile interleaved with QK of the next; V group 0 already on its way into fr[0]
-    auto mm_both = [&](f32x16 (&s)[2], const bf16x8 (&pf)[4]) {
-        zero_s(s);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            read_kg(i, 1);
-            mfma_vg(i, 0, pf);
-            __builtin_amdgcn_sched_barrier(0);
-            if (i + 1 < 4) read_vg(i + 1, 0);
-            mfma_kg(i, 1, s);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
+    bf16x8 no_p[4];
+    auto qk = [&](f32x16 (&s)[2]) __attribute__((always_inline)) { zero_s(s); run_frags(0, s, no_p); };
+    auto pv = [&](const bf16x8 (&pf)[4]) __attribute__((always_inline)) { f32x16 no_s[2]; run_frags(1, no_s, pf); };
+    auto mm_both = [&](f32x16 (&s)[2], const bf16x8 (&pf)[4]) __attribute__((always_inline)) { zero_s(s); run_frags(2, s, pf); };
     auto mask = [&](f32x16 (&s)[2], int slot) {
         const unsigned tok_base = lds0 + kTokOff + slot * TK * 4;
 #pragma unroll
