@@ -4,9 +4,9 @@
 // One wavefront per (batch, head, segment) row.  The row lives in registers (lane l owns blocks
 // l, l+64, ...).  Scores are mapped to order-preserving unsigned keys; the k-th largest key is found
 // by an MSB-first radix search (one wave-wide count per bit: a compare per key, the lane masks counted on the
-// scalar unit); everything above it is taken, ties at
+// scalar unit) that stops at the first bit whose count is exactly k; everything above it is taken, ties at
 // the threshold go to the smallest indices, and the result is compacted in index order, so the
-// list comes out ascending.
+// list comes out ascending.  Long rows are first thinned to the few keys that can be among the k largest.
 #include "kernels.h"
 
 namespace cp {
@@ -43,7 +43,111 @@ __device__ __forceinline__ int wave_sum(int v) {
     return v;
 }
 
+// The k-th largest of the wave's 64 * N keys (padding keys are 0 and never counted): MSB-first radix search, one
+// wave-wide count per bit (a compare per key, the lane masks counted on the scalar unit).  It stops at the first
+// bit whose count is exactly k: the keys at or above that trial value are then the k largest (the k-th and the
+// (k+1)-th differ), and the value returned separates them just as well as the k-th key itself.
+// Always: count(key >= result) >= k, provided k keys are non-zero.
+template <int N>
+__device__ __forceinline__ uint32_t kth_largest(const uint32_t (&key)[N], int k) {
+    uint32_t thr = 0;
+    for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t trial = thr | (1u << bit);
+        int c = 0;
+#pragma unroll
+        for (int m = 0; m < N; ++m) c += (int)__popcll(__ballot(key[m] >= trial));
+        if (c >= k) thr = trial;
+        if (c == k) break;
+    }
+    return thr;
+}
+
+// Writes, in slot order (slot m, then lane), the index of every key above thr and of the first keys equal to thr
+// until k are taken; returns how many were written.  index(m) = the block index of the lane's key m.
+template <int N, typename Index>
+__device__ __forceinline__ int take_largest(const uint32_t (&key)[N], uint32_t thr, int k, int n_slots, int lane,
+                                            int32_t* out, Index index) {
+    int above = 0;
+#pragma unroll
+    for (int m = 0; m < N; ++m) above += (int)__popcll(__ballot(key[m] > thr));
+    int ties_left = k - above;                         // the keys equal to thr that still fit (0 if none is)
+    int written = 0;
+#pragma unroll
+    for (int m = 0; m < N; ++m) {
+        if (m >= n_slots) break;                        // wave-uniform
+        const bool valid = key[m] != 0u;                // padding keys are 0, the key of a score never is
+        const bool tie = valid && key[m] == thr;
+        const unsigned long long tie_mask = __ballot(tie);
+        const int tie_rank = __popcll(tie_mask & ((1ull << lane) - 1ull));
+        const bool take = valid && (key[m] > thr || (tie && tie_rank < ties_left));
+        const unsigned long long take_mask = __ballot(take);
+        if (take) out[written + __popcll(take_mask & ((1ull << lane) - 1ull))] = index(m);
+        written += __popcll(take_mask);
+        ties_left -= min(ties_left, (int)__popcll(tie_mask));
+        __builtin_amdgcn_sched_barrier(0);              // keeps the ballot masks of one step from piling up in SGPRs
+    }
+    return written;
+}
+
+constexpr int kCandPerLane = 4;                         // the prefilter keeps at most 64 * 4 candidates per row
+constexpr int kPrefilterMaxK = 128;                     // and is used for k up to half that many buckets
+
+// The search over one row with PER_LANE keys per lane (64 * PER_LANE >= the row's candidates).
+// Long rows are thinned first: the lane's keys fall into four buckets (slot mod 4), so the wave has 256 bucket
+// maxima; the k-th largest of them, T, has at least k keys at or above it, so the k largest keys of the row are
+// among the keys >= T (about k..1.4 k of them when large scores are spread over the lanes).  Those are compacted
+// in index order into the wave's LDS region (at most 4 per lane) and the exact search runs on them: the same list,
+// ties included, with a fraction of the compares.  A row with more than 256 keys >= T (many equal scores) is
+// searched in full.
 template <int PER_LANE, bool SHARED>
+__device__ __forceinline__ int select_row(const SelectArgs& a, long long row, int j, int n_cand, int kj, int lane,
+                                          int32_t* out, uint2* cand) {
+    uint32_t key[PER_LANE];
+#pragma unroll
+    for (int m = 0; m < PER_LANE; ++m) {
+        const int i = m * 64 + lane;
+        const uint32_t kx = row_key<SHARED>(a, row, j, min(i, a.n2 - 1));   // unconditional load: no per-element exec masks to keep
+        key[m] = (i < n_cand) ? kx : 0u;                   // 0 is below every trial threshold: never counted
+    }
+    if (PER_LANE > kCandPerLane && kj <= kPrefilterMaxK) {
+        uint32_t top[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int m = 0; m < PER_LANE; ++m) top[m & 3] = max(top[m & 3], key[m]);
+        const uint32_t T = kth_largest<4>(top, kj);        // > 0: the row has kj <= 128 valid keys in distinct buckets
+        int total = 0;
+#pragma unroll
+        for (int m = 0; m < PER_LANE; ++m) total += (int)__popcll(__ballot(key[m] >= T));
+        if (T != 0u && total <= 64 * kCandPerLane) {        // wave-uniform
+            int base = 0;
+#pragma unroll
+            for (int m = 0; m < PER_LANE; ++m) {
+                const bool in = key[m] >= T;
+                const unsigned long long mask = __ballot(in);
+                if (in) cand[base + __popcll(mask & ((1ull << lane) - 1ull))] = make_uint2(key[m], (unsigned)(m * 64 + lane));
+                base += (int)__popcll(mask);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // the wave reads back what its own lanes wrote: LDS operations of a wave complete in order
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            uint32_t ck[kCandPerLane]; int ci[kCandPerLane];
+#pragma unroll
+            for (int c = 0; c < kCandPerLane; ++c) {
+                const int pos = c * 64 + lane;
+                const uint2 e = cand[min(pos, 64 * kCandPerLane - 1)];
+                ck[c] = pos < total ? e.x : 0u; ci[c] = (int)e.y;
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // before the region is written for the wave's next row
+            const uint32_t thr = kth_largest<kCandPerLane>(ck, kj);
+            return take_largest<kCandPerLane>(ck, thr, kj, (total + 63) / 64, lane, out, [&](int c) { return ci[c]; });
+        }
+    }
+    const uint32_t thr = kth_largest<PER_LANE>(key, kj);
+    return take_largest<PER_LANE>(key, thr, kj, (n_cand + 63) / 64, lane, out, [&](int m) { return m * 64 + lane; });
+}
+
+// MAX_PER_LANE: 64 * MAX_PER_LANE >= n2, a multiple of 8.  A row early in the sequence has few candidates: the
+// search is compiled for eight row lengths (eighths of the maximum) and a wave takes the shortest that holds its row.
+template <int MAX_PER_LANE, bool SHARED>
 __global__ __launch_bounds__(256) void select_kernel(SelectArgs a) {
     const int lane = threadIdx.x & 63;
     const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -55,42 +159,22 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a) {
     const int n_cand = diag_lo - n_local;
     const int kj = min(a.budget, n_cand);
     int32_t* out = a.idx + row * a.list_len;
+    __shared__ uint2 cand_all[4][64 * kCandPerLane];
+    uint2* cand = cand_all[threadIdx.x >> 6];
 
-    uint32_t key[PER_LANE];
-#pragma unroll
-    for (int m = 0; m < PER_LANE; ++m) {
-        const int i = m * 64 + lane;
-        const uint32_t kx = row_key<SHARED>(a, row, j, min(i, a.n2 - 1));   // unconditional load: no per-element exec masks to keep
-        key[m] = (i < n_cand) ? kx : 0u;                   // 0 is below every trial threshold: never counted
-    }
     int written = 0;
     if (kj > 0) {
-        uint32_t thr = 0;
-        for (int bit = 31; bit >= 0; --bit) {
-            const uint32_t trial = thr | (1u << bit);
-            int c = 0;                                  // wave-wide count on the scalar unit: one compare per key
-#pragma unroll
-            for (int m = 0; m < PER_LANE; ++m) c += (int)__popcll(__ballot(key[m] >= trial));   // trial >= 1: padding keys stay out
-            if (c >= kj) thr = trial;
-        }
-        int above = 0;
-#pragma unroll
-        for (int m = 0; m < PER_LANE; ++m) above += (int)__popcll(__ballot(key[m] > thr));
-        int ties_left = kj - above;                    // >= 1 by construction of thr
-#pragma unroll
-        for (int m = 0; m < PER_LANE; ++m) {
-            if (m * 64 >= n_cand) break;                // wave-uniform
-            const int i = m * 64 + lane;
-            const bool valid = key[m] != 0u;            // padding keys are 0, the key of a score never is
-            const bool tie = valid && key[m] == thr;
-            const unsigned long long tie_mask = __ballot(tie);
-            const int tie_rank = __popcll(tie_mask & ((1ull << lane) - 1ull));
-            const bool take = valid && (key[m] > thr || (tie && tie_rank < ties_left));
-            const unsigned long long take_mask = __ballot(take);
-            if (take) out[written + __popcll(take_mask & ((1ull << lane) - 1ull))] = i;
-            written += __popcll(take_mask);
-            ties_left -= min(ties_left, (int)__popcll(tie_mask));
-            __builtin_amdgcn_sched_barrier(0);          // keeps the ballot masks of one step from piling up in SGPRs
+        constexpr int E = MAX_PER_LANE / 8;
+        const int eighths = (n_cand + 64 * E - 1) / (64 * E);          // wave-uniform, 1 .. 8
+        switch (eighths) {
+            case 1: written = select_row<1 * E, SHARED>(a, row, j, n_cand, kj, lane, out, cand); break;
+            case 2: written = select_row<2 * E, SHARED>(a, row, j, n_cand, kj, lane, out, cand); break;
+            case 3: written = select_row<3 * E, SHARED>(a, row, j, n_cand, kj, lane, out, cand); break;
+            case 4: written = select_row<4 * E, SHARED>(a, row, j, n_cand, kj, lane, out, cand); break;
+            case 5: written = select_row<5 * E, SHARED>(a, row, j, n_cand, kj, lane, out, cand); break;
+            case 6: written = select_row<6 * E, SHARED>(a, row, j, n_cand, kj, lane, out, cand); break;
+            case 7: written = select_row<7 * E, SHARED>(a, row, j, n_cand, kj, lane, out, cand); break;
+            default: written = select_row<8 * E, SHARED>(a, row, j, n_cand, kj, lane, out, cand); break;
         }
     }
     // local blocks then the segment's own blocks
@@ -142,7 +226,9 @@ __global__ __launch_bounds__(kWideThreads) void select_wide_kernel(SelectArgs a)
             int c = 0;
 #pragma unroll
             for (int m = 0; m < kWidePerThread; ++m) c += (key[m] >= trial) ? 1 : 0;
-            if (block_sum(c) >= kj) thr = trial;
+            const int t = block_sum(c);
+            if (t >= kj) thr = trial;
+            if (t == kj) break;                            // uniform: exactly the list, see select_row
         }
         int above = 0;
 #pragma unroll

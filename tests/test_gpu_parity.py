@@ -126,6 +126,27 @@ def test_select_long_rows_with_ties(n_blocks, budget):
     H.check_selection(Sd, idx_o, cnt_o, idx_g, cnt_g, w, exact=True)
 
 
+@pytest.mark.parametrize("budget", [1, 32, 64, 128, 129])
+@pytest.mark.parametrize("layout", ["spread", "one_lane", "few_distinct"])
+def test_select_rows_of_2048_blocks(budget, layout):
+    """Rows of up to 2048 candidates with distinct scores: large scores spread over the row, large scores only at
+    block indices = 5 mod 64 (all in one lane of the kernel's wave, so that thinning the row by per-lane maxima
+    keeps too many candidates and the kernel must search the whole row), and a row whose large scores are few."""
+    b = 64
+    w = H.small_workload("sel2k", 1, 2, 1, 2048 * b, 512, b, budget, 1)
+    g = np.random.default_rng(100 * budget + len(layout))
+    Sd = g.random((1, 2, w.n_segments, w.n_blocks), dtype=np.float32) * 1e-3
+    if layout == "one_lane":
+        Sd[..., 5::64] += 1.0
+    elif layout == "few_distinct":
+        Sd[..., ::97] += 0.5
+    idx_o, cnt_o = O.select(Sd, w.segment_size, w.block_size, w.budget_blocks, w.local_blocks)
+    q = torch.empty((1, 2, w.seq_len, 128), dtype=torch.bfloat16, device=DEV)
+    k = torch.empty((1, 1, w.seq_len, 128), dtype=torch.bfloat16, device=DEV)
+    idx_g, cnt_g = H.gpu_select(w, q, k, torch.from_numpy(Sd).to(DEV))
+    H.check_selection(Sd, idx_o, cnt_o, idx_g, cnt_g, w, exact=True)
+
+
 @pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
 def test_estimate_then_select_tie_band(case):
     w, q, k, v = make(case)
