@@ -164,6 +164,7 @@ struct ScoreArgs {
     float* stats;                          // bf16 path: per-chunk softmax statistics (see score_stats_kernel)
     int hq, hkv, n1, n2, r, domain;
     int nchunk, n1_pad;
+    int parts;                             // bf16 path: waves that share 16 segments and split the tiles of a chunk (1, 2, 4, 8)
     float scale, alpha;
 };
 constexpr int kScoreWaves = 8;             // waves per workgroup of the bf16 score kernels, 16 segments each
@@ -300,6 +301,7 @@ struct ScoreTile {
 // The part both kernels share: the workgroup's coordinates, the B operand, the staged A tiles.
 struct ScoreCtx {
     int lane, wave, l32, hh;
+    int part;                                               // tiles nt = part (mod parts) of the chunk are this wave's
     int chunk, j0, seg, rep, h, bb_;
     int i_begin, i_end, ntile;                              // blocks of the chunk, tiles of 32
     long long qrow0;                                        // row of segment 0 of this (batch, head) in scores
@@ -314,7 +316,11 @@ struct ScoreCtx {
 __device__ __forceinline__ void score_setup(const ScoreArgs& a, ScoreCtx& c, unsigned lds0) {
     const int tid = threadIdx.x;
     c.lane = tid & 63; c.wave = tid >> 6; c.l32 = c.lane & 31; c.hh = c.lane >> 5;
-    c.chunk = blockIdx.x; c.j0 = blockIdx.y * kScoreSegPerWg + 16 * c.wave;
+    c.chunk = blockIdx.x;
+    // a short sequence has fewer than 8 x 16 segments: waves then share their 16 segments and split the tiles
+    const int seg_waves = kScoreWaves / a.parts;
+    c.part = c.wave / seg_waves;
+    c.j0 = blockIdx.y * kScoreSegPerWg + 16 * (c.wave % seg_waves);
     c.h = blockIdx.z % a.hq; c.bb_ = blockIdx.z / a.hq;
     c.seg = c.j0 + (c.l32 >> 1); c.rep = c.l32 & 1;
     c.i_begin = c.chunk * kScoreChunk; c.i_end = min(a.n2, c.i_begin + kScoreChunk);
@@ -375,10 +381,11 @@ __device__ __forceinline__ void score_tile(const ScoreCtx& c, int nt, f32x16 (&z
         }
     }
 }
-// statistics of chunk cc, product b2, column col: stats[(((bh * nchunk + cc) * 2 + b2) * 2 + which) * cols + col]
+// statistics of chunk part cc (= chunk * parts + part), product b2, column col:
+// stats[(((bh * nchunk * parts + cc) * 2 + b2) * 2 + which) * cols + col]
 __device__ __forceinline__ long long stats_index(const ScoreArgs& a, const ScoreCtx& c, int cc, int b2, int which) {
     const long long cols = 2LL * a.n1_pad;
-    return ((((long long)blockIdx.z * a.nchunk + cc) * 2 + b2) * 2 + which) * cols + 2 * c.seg + c.rep;
+    return ((((long long)blockIdx.z * (a.nchunk * a.parts) + cc) * 2 + b2) * 2 + which) * cols + 2 * c.seg + c.rep;
 }
 
 __global__ __launch_bounds__(64 * kScoreWaves, 4) void score_stats_kernel(ScoreArgs a) {
@@ -397,6 +404,7 @@ __global__ __launch_bounds__(64 * kScoreWaves, 4) void score_stats_kernel(ScoreA
             score_chunk_ready();
             if (nt + 2 < c.ntile) score_load_piece(a, c, (nt >> 1) + 1);
         }
+        if ((nt & (a.parts - 1)) != c.part) continue;       // another wave's tile
         f32x16 z[2];
         score_tile(c, nt, z);
         const int i0 = c.i_begin + nt * ScoreTile::kTileBlocks + 4 * c.hh;
@@ -440,8 +448,8 @@ __global__ __launch_bounds__(64 * kScoreWaves, 4) void score_stats_kernel(ScoreA
     for (int b2 = 0; b2 < 2; ++b2) {
         const float lt = halves_sum(l[b2]);
         if (c.hh == 0) {
-            a.stats[stats_index(a, c, c.chunk, b2, 0)] = m[b2];
-            a.stats[stats_index(a, c, c.chunk, b2, 1)] = lt;
+            a.stats[stats_index(a, c, c.chunk * a.parts + c.part, b2, 0)] = m[b2];
+            a.stats[stats_index(a, c, c.chunk * a.parts + c.part, b2, 1)] = lt;
         }
     }
 }
@@ -473,7 +481,7 @@ __global__ __launch_bounds__(64 * kScoreWaves, 4) void score_write_kernel(ScoreA
     // merge the chunk statistics of the lane's column: the lane does the product b2 = hh, the same column's
     // lane in the other wave half does the other one (domain 1: chunks past the workgroup's last visible
     // block were never written)
-    const int ncc = a.domain == 0 ? a.nchunk : (c.vis_wg + kScoreChunk - 1) / kScoreChunk;
+    const int ncc = (a.domain == 0 ? a.nchunk : (c.vis_wg + kScoreChunk - 1) / kScoreChunk) * a.parts;
     float mx[2], inv[2];
     {
         float M = -INFINITY, L = 0.f;
@@ -506,6 +514,7 @@ __global__ __launch_bounds__(64 * kScoreWaves, 4) void score_write_kernel(ScoreA
             score_chunk_ready();
             if (nt + 2 < c.ntile) score_load_piece(a, c, (nt >> 1) + 1);
         }
+        if ((nt & (a.parts - 1)) != c.part) continue;       // another wave's tile
         f32x16 z[2];
         const bool unseen = c.i_begin + nt * ScoreTile::kTileBlocks >= c.vis_wave_max;   // by every segment of the wave
         if (!unseen) score_tile(c, nt, z);
@@ -589,9 +598,13 @@ hipError_t launch_pool(const Shape& sh, const void* q, const void* k, void* qrep
     return hipGetLastError();
 }
 
+// waves of a score workgroup that share their segments: all eight take different segments unless the sequence
+// has too few of them
+static int score_parts(int n1) { return n1 <= 16 ? 8 : n1 <= 32 ? 4 : n1 <= 64 ? 2 : 1; }
+
 size_t score_stats_bytes(const Shape& sh) {
     if (sh.dtype != 1) return 0;
-    const size_t nchunk = (sh.n2 + kScoreChunk - 1) / kScoreChunk;
+    const size_t nchunk = (size_t)((sh.n2 + kScoreChunk - 1) / kScoreChunk) * score_parts(sh.n1);
     const size_t n1_pad = (size_t)((sh.n1 + kScoreSegPerWg - 1) / kScoreSegPerWg) * kScoreSegPerWg;
     return (size_t)sh.batch * sh.hq * nchunk * 2 * 2 * (2 * n1_pad) * sizeof(float);
 }
@@ -604,6 +617,7 @@ hipError_t launch_score(const Shape& sh, const void* qrep, const void* krep, con
     a.scale = sh.score_scale; a.alpha = sh.alpha;
     a.nchunk = (sh.n2 + kScoreChunk - 1) / kScoreChunk;
     a.n1_pad = (sh.n1 + kScoreSegPerWg - 1) / kScoreSegPerWg * kScoreSegPerWg;
+    a.parts = score_parts(sh.n1);
     if (sh.dtype == 1) {
         if ((long long)sh.batch * sh.hq > 65535) return hipErrorInvalidValue;
         dim3 grid_m(a.nchunk, a.n1_pad / kScoreSegPerWg, sh.batch * sh.hq);

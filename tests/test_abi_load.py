@@ -49,8 +49,9 @@ def test_sizes():
     assert B.critiprefill_list_len(p) == 4 + 1 + 4
     n1, n2 = 8, 32
     # representatives of 4 query heads x n1 segments and 2 KV heads x n2 blocks, then the score statistics of the
-    # bf16 path: per head and chunk of 256 blocks, 2 products x (max, sum) x 2 representatives x 128-padded segments
-    assert B.critiprefill_workspace_bytes(p) == (4 * n1 + 2 * n2) * 2 * 128 * 2 + 4 * 1 * 2 * 2 * (2 * 128) * 4
+    # bf16 path: per head and chunk of 256 blocks (one chunk here, cut in 8 parts because a sequence of at most 16
+    # segments lets the 8 waves of a workgroup share them), 2 products x (max, sum) x 2 representatives x 128-padded segments
+    assert B.critiprefill_workspace_bytes(p) == (4 * n1 + 2 * n2) * 2 * 128 * 2 + 4 * (1 * 8) * 2 * 2 * (2 * 128) * 4
     p = _params(dtype=B.CP_DTYPE_FP32, seq_len=1000)
     n1, n2 = 8, 32
     assert B.critiprefill_workspace_bytes(p) == (4 * n1 + 2 * n2) * 2 * 128 * 4
