@@ -355,7 +355,8 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=10,
+                    help="untimed steps; the attention kernel keeps getting faster over the first ~8 launches after an idle phase")
     ap.add_argument("--workload", default="c3_llama3_8b_128k")
     ap.add_argument("--dense-steps", type=int, default=3)
     ap.add_argument("--budgets", default="512,1024,4096", help="token budgets of the multi-layer workload, one JSON line each")
