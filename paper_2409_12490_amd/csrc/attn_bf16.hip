@@ -129,14 +129,31 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
         const int bkvh = x % bkv, gq = x / bkv;
         bb = bkvh / a.hkv; h = (bkvh % a.hkv) * G + gq;
     } else {
-        // (batch, KV head) groups run one after another; inside a group every XCD gets a contiguous
-        // range of segments, with the query tiles and query heads of one segment adjacent.
-        const int per_group = G * a.n1 * a.qtiles;
+        // (batch, KV head) groups run one after another.  Workgroups reach the compute units round-robin and in
+        // order: workgroup x + 256 follows workgroup x on the same unit and starts only after every workgroup
+        // before it has started, so a round of 256 workgroups lasts as long as its slowest member.  The first
+        // query tile of a segment sees fewer keys than the last (the plain order, both tiles in every round, left
+        // the units with the short tiles idle 6 us per item; measured with per-wave time stamps), so a round
+        // takes 256 (query head, segment) pairs at ONE query tile and the next round the same pairs at the next
+        // tile.  Inside a round every XCD (workgroup id mod 8) gets 32 consecutive pairs: the query heads of a
+        // few neighbouring segments.
+        constexpr int kRound = 256;
+        const int pairs = G * a.n1;
+        const int per_group = pairs * a.qtiles;
         const int grp = blockIdx.x / per_group;
-        int lid = blockIdx.x % per_group;
-        if ((per_group & 7) == 0) lid = (lid & 7) * (per_group >> 3) + (lid >> 3);
-        qt = lid % a.qtiles; lid /= a.qtiles;
-        const int gq = lid % G; j = lid / G;
+        const int x = blockIdx.x % per_group;
+        const int full = pairs / kRound * kRound;                // pairs that fill whole rounds
+        int u;
+        if (x < full * a.qtiles) {
+            const int y = x % (kRound * a.qtiles), pos = y % kRound;
+            qt = y / kRound;
+            u = x / (kRound * a.qtiles) * kRound + (pos & 7) * (kRound / 8) + (pos >> 3);
+        } else {
+            const int rest = pairs - full, y = x - full * a.qtiles;
+            qt = y / rest;
+            u = full + y % rest;
+        }
+        const int gq = u % G; j = u / G;
         bb = grp / a.hkv; h = (grp % a.hkv) * G + gq;
     }
     const int g = h / G;
