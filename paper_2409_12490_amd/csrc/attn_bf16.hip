@@ -168,6 +168,21 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
     const uint16_t* kp = uniform_ptr(a.k + bb * a.ks0 + g * a.ks1);
     const uint16_t* vp = uniform_ptr(a.v + bb * a.ks0 + g * a.ks1);
 
+    // ---- the virtual token list --------------------------------------------------------------
+    // Its loads are issued before those of Q (the scheduling barrier keeps the compiler from hoisting Q's loads
+    // above them): loads return in order, the list row comes from L2 / Infinity Cache (the selection has just
+    // written it) and the first K/V tiles cannot be asked for before it is here, while Q comes from HBM and is
+    // not needed before those tiles have landed.
+    int count = 0, list_first = -1;
+    const int32_t* list = nullptr;
+    if (!DENSE) {
+        const long long lrow = a.shared_lists ? ((long long)bb * a.hkv + g) * a.n1 + j : ((long long)bb * a.hq + h) * a.n1 + j;
+        list = a.idx + lrow * a.list_len;
+        // the whole row (its pitch is list_len) is copied, so that its loads do not wait for the count
+        if (tid < a.list_len) list_first = list[tid];
+        count = min(max(a.cnt[lrow], 0), a.list_len);             // a bad count must not run past the list's LDS region
+        __builtin_amdgcn_sched_barrier(0);
+    }
     // ---- Q fragments (B operand: column = query l32, 8 channels at 16*ks + 8*hh) ---------------
     const int qpos = wq_lo + l32;
     bf16x8 qf[8];
@@ -182,14 +197,9 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(ArgsB a) {
         }
     }
 
-    // ---- the virtual token list --------------------------------------------------------------
-    int count = 0;
     if (!DENSE) {
-        const long long lrow = a.shared_lists ? ((long long)bb * a.hkv + g) * a.n1 + j : ((long long)bb * a.hq + h) * a.n1 + j;
-        const int32_t* list = a.idx + lrow * a.list_len;
-        // the whole row (its pitch is list_len) is copied, so that its loads do not wait for the count
-        for (int x = tid; x < a.list_len; x += 512) *LDS_PTR(int, lds0 + kListOff + x * 4) = list[x];
-        count = min(max(a.cnt[lrow], 0), a.list_len);             // a bad count must not run past the list's LDS region
+        if (tid < a.list_len) *LDS_PTR(int, lds0 + kListOff + tid * 4) = list_first;
+        for (int x = tid + 512; x < a.list_len; x += 512) *LDS_PTR(int, lds0 + kListOff + x * 4) = list[x];
     }
     __syncthreads();
     // positions 0 .. total-1 of the listed blocks laid end to end (host checks count * b < 2^31)

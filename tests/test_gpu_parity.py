@@ -172,6 +172,31 @@ def test_sparse_attention_with_checker_lists(case):
     assert H.max_abs(lse.cpu().numpy(), lse_ref) <= (2e-2 if w.dtype == "bf16" else 1e-4)
 
 
+@pytest.mark.parametrize("shape", [(4, 1, 35700, 512, 64), (2, 2, 66000, 256, 32), (3, 1, 70000, 1024, 64)],
+                         ids=["280_pairs_2_tiles", "516_pairs_1_tile", "207_pairs_4_tiles"])
+def test_sparse_attention_workgroup_order_covers_every_item(shape):
+    """More (head, segment) pairs than one round of 256 workgroups holds, plus a remainder, at 1, 2 and 4 query tiles
+    per segment: every output row is written (the output starts as NaN) and sampled segments, among them those around
+    the border between the full rounds and the remainder, match the checker."""
+    Hq, Hkv, n, s, b = shape
+    w = H.small_workload("order", 1, Hq, Hkv, n, s, b, 4, 1)
+    q, k, v = synth.make_qkv(w, threads=8)
+    g = np.random.default_rng(3)
+    Sd = g.random((1, Hq, w.n_segments, w.n_blocks), dtype=np.float32)       # any scores will do: the lists are the input here
+    idx_o, cnt_o = O.select(Sd, s, b, w.budget_blocks, w.local_blocks)
+    out, lse = H.gpu_sparse(w, q.to(DEV), k.to(DEV), v.to(DEV), torch.from_numpy(idx_o).to(DEV), torch.from_numpy(cnt_o).to(DEV))
+    out = out.float().cpu().numpy()
+    assert not np.isnan(out).any() and not np.isnan(lse.cpu().numpy()).any()
+    G = Hq // Hkv
+    border = 256 // G                                                       # segment of the first pair past one full round
+    segs = sorted({0, 1, border - 1, border, border + 1, w.n_segments // 2, w.n_segments - 2, w.n_segments - 1} & set(range(w.n_segments)))
+    todo = [(0, h, j) for h in range(Hq) for j in segs]
+    o_ref, _ = O.sparse_attention(synth.to_f64(q), synth.to_f64(k), synth.to_f64(v), idx_o, cnt_o, s, b, segments=todo)
+    for (_, h, j) in todo:
+        rows = slice(j * s, min(n, (j + 1) * s))
+        assert H.max_abs(out[0, h, rows], o_ref[0, h, rows]) <= 2e-2, (h, j)
+
+
 @pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
 def test_shared_lists_per_kv_head(case):
     """One list per KV head from the maximum of the group's scores: selection bit-exact on the same fp32
