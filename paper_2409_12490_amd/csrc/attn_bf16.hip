@@ -15,7 +15,7 @@
 //
 // One wave cannot overlap its own MFMA and VALU work to any useful degree on this hardware, two waves
 // on one SIMD can.  So every SIMD holds two waves (w and w+4).  A wave alternates between a matrix phase
-// MM(t) = PV(t-1) interleaved with QK(t) (36 independent-enough MFMAs that keep the matrix pipe full) and the
+// MM(t) = PV(t-1) interleaved with QK(t) (32 independent-enough MFMAs that keep the matrix pipe full) and the
 // softmax phase SM(t); the two waves of a SIMD run half a period apart:
 //     waves 0-3:  MM(t)  SM(t)                   waves 4-7:  SM(t)  MM(t+1)
 // which puts the softmax VALU work of one wave under the MFMA work of the other.
